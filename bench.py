@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused Harris coarsity kernel on one MI355X.
+
+A step is one pass of the whole pipeline (grayscale, Sobel pair, products, 3x3 sums,
+coarsity: one kernel launch) over one synthetic 3x1536x2560 float32 image that is
+already resident in device memory.  Successive steps use different input/result
+buffers, rotating over more than 1 GiB, so that no step finds its image in the
+256 MB last-level cache left there by an earlier step.
+
+Prints one JSON line: throughput in Mpixels/s (input pixels), the roofline object
+for the kernel (algorithmic bytes / launch duration against 8 TB/s of HBM) and the
+CPU oracle timed on this host as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
+WORKLOAD = "noise_f32_1536x2560"
+K_COARSITY = 0.04
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=720)
+    ap.add_argument("--warmup", type=int, default=72)
+    ap.add_argument("--workload", default=WORKLOAD, help="one of harris_inputs.WORKLOADS (default: the headline one)")
+    ap.add_argument("--rotate-bytes", type=float, default=float(1 << 30), help="distinct buffer bytes to rotate over")
+    ap.add_argument("--px", type=int, default=0)
+    ap.add_argument("--rows-per-band", type=int, default=0)
+    ap.add_argument("--prefetch", type=int, default=0)
+    ap.add_argument("--waves-per-block", type=int, default=0)
+    ap.add_argument("--flags", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--warm-cache", action="store_true", help="reuse one buffer pair (cache-resident; not the roofline number)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)")
+
+    import numpy as np
+    import torch
+    import harris_inputs
+    import paper_2212_12035_amd as pkg
+
+    if not os.path.exists(pkg.library_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    lib = pkg.load_library()
+
+    gen, seed, B, H, W, dt = harris_inputs.WORKLOADS[args.workload]
+    is_u8 = dt == "u8"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    host = harris_inputs.make(args.workload)
+    n, m = H - 4, W - 4
+    in_bytes = B * 3 * H * W * (1 if is_u8 else 4)
+    out_bytes = B * n * m * 4
+    algo_bytes = in_bytes + out_bytes                      # each input element read once, each result written once
+    pixels = B * H * W
+
+    # Rotating buffer pairs.  Pair 0 holds the seeded image; pair i holds the same image
+    # rolled down by i rows (same statistics, different addresses).
+    n_pairs = 1 if args.warm_cache else max(2, int(-(-args.rotate_bytes // algo_bytes)))
+    free_b, _ = torch.cuda.mem_get_info(dev)
+    n_pairs = max(1, min(n_pairs, int(0.8 * free_b // algo_bytes)))
+    base = torch.from_numpy(host).to(dev)
+    ins = [base] + [torch.roll(base, shifts=i, dims=2) for i in range(1, n_pairs)]
+    outs = [torch.empty((B, n, m), dtype=torch.float32, device=dev) for _ in range(n_pairs)]
+
+    tuning = pkg.HarrisTuning(args.px, args.rows_per_band, args.prefetch, args.waves_per_block, args.flags)
+    shape, n_blocks = pkg.harris_plan(pkg.HARRIS_U8 if is_u8 else pkg.HARRIS_F32, B, H, W, tuning=tuning)
+    stream = torch.cuda.current_stream(dev)
+    sptr = ctypes.c_void_p(stream.cuda_stream)
+    dtype_code = pkg.HARRIS_U8 if is_u8 else pkg.HARRIS_F32
+    calls = [(ctypes.c_void_p(i.data_ptr()), ctypes.c_void_p(o.data_ptr())) for i, o in zip(ins, outs)]
+    tref = ctypes.byref(tuning)
+    fn = lib.harris_coarsity_ex
+
+    def step(i):
+        a, o = calls[i % n_pairs]
+        rc = fn(a, dtype_code, B, H, W, K_COARSITY, 1.0, 0, o, tref, sptr)
+        if rc != 0:
+            raise RuntimeError(pkg.harris_strerror(rc))
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize(dev)
+
+    # Timed region: exactly `steps` launches, wall clock between synchronisations, and a
+    # pair of HIP events on the launch stream for the GPU-side duration.
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize(dev)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for i in range(args.steps):
+        step(i)
+    ev1.record(stream)
+    torch.cuda.synchronize(dev)
+    t1 = time.perf_counter()
+    wall_ms = (t1 - t0) * 1e3
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall_ms / args.steps
+    launch_us = gpu_ms * 1e3 / args.steps                 # average per launch over the timed region
+
+    # Single-launch durations (event pair around each launch), for information.
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(args.steps, 60))]
+    for i, (a, b) in enumerate(pairs):
+        a.record(stream); step(i); b.record(stream)
+    torch.cuda.synchronize(dev)
+    singles = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)
+    single_med_us = singles[len(singles) // 2]
+
+    # Correctness of what was timed: pair 0 against the oracle (also the CPU baseline).
+    got = outs[0].cpu().numpy()
+    cpu = None
+    max_err = bound = None
+    if not args.no_cpu_baseline:
+        from oracle import harris_oracle
+        nt = harris_oracle.hardware_threads()
+        sample = host if B == 1 else host[:1]
+        spx = sample.shape[0] * H * W
+        harris_oracle.harris(sample, K_COARSITY, nthreads=nt)            # page in
+        reps_all, reps_one = 5, 2
+        ta = []
+        for _ in range(reps_all):
+            s = time.perf_counter(); want = harris_oracle.harris(sample, K_COARSITY, nthreads=nt); ta.append(time.perf_counter() - s)
+        to = []
+        for _ in range(reps_one):
+            s = time.perf_counter(); harris_oracle.harris(sample, K_COARSITY, nthreads=1); to.append(time.perf_counter() - s)
+        ta.sort(); to.sort()
+        max_err = float(np.abs(got[:sample.shape[0]] - want).max())
+        bound = 1e-4 * float(np.abs(want).max()) + 1e-6
+        cpu = {"value": round(spx / ta[len(ta) // 2] / 1e6, 2), "unit": "Mpixels/s", "cores": nt, "kind": "oracle",
+               "sample": "%d image(s) of %s, median of %d runs on %d threads" % (sample.shape[0], args.workload, reps_all, nt),
+               "value_1_thread": round(spx / to[len(to) // 2] / 1e6, 2)}
+
+    achieved = algo_bytes / (launch_us * 1e-6) / 1e9
+    result = {
+        "metric": "harris_coarsity_throughput",
+        "value": round(pixels / (ms_per_step * 1e-3) / 1e6, 1),
+        "unit": "Mpixels/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": B, "H": H, "W": W, "input": dt, "k": K_COARSITY,
+                   "buffer_pairs": n_pairs, "cache": "warm" if args.warm_cache else "cold (rotating buffers)",
+                   "launch": shape, "workgroups": n_blocks},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": algo_bytes,
+                     "launch_us_avg_over_timed_region": round(launch_us, 3),
+                     "launch_us_single_median": round(single_med_us, 3)},
+        "cpu_baseline": cpu,
+        "max_abs_err_vs_oracle": max_err, "err_bound": bound,
+    }
+    print(json.dumps(result))
+    if max_err is not None and not max_err <= bound:
+        sys.exit("bench: GPU result differs from the oracle by %g (bound %g)" % (max_err, bound))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,133 @@
+/*
+ * libharris: Harris corner-detection coarsity on one AMD MI355X (gfx950).
+ *
+ * The operation is the Harris operator of the thesis's chapter 4, section 4.2
+ * (listing "Harris operator algorithm in Halide", and the Rise listings
+ * "High-level pointwise operators", "High-level stencil operators" and
+ * "High-level Harris operator"):
+ *
+ *   gray = 0.299 R + 0.587 G + 0.114 B
+ *   Ix   = Sx gray,  Iy = Sy gray          3x3 Sobel correlations, valid region
+ *   Ixx  = Ix*Ix, Ixy = Ix*Iy, Iyy = Iy*Iy
+ *   Sxx, Sxy, Syy = 3x3 window sums of Ixx, Ixy, Iyy, valid region
+ *   out  = (Sxx*Syy - Sxy*Sxy) - k * (Sxx + Syy)^2
+ *
+ * with no border padding: a 3 x H x W image gives an (H-4) x (W-4) result, and
+ * out[y][x] depends on rgb[:, y..y+4, x..x+4].  All of it runs in one fused GPU
+ * kernel; no intermediate image is written to device memory.
+ *
+ * Conventions common to every entry point
+ *   - rgb and out are DEVICE pointers owned by the caller.  The library allocates
+ *     nothing, keeps no state between calls and is re-entrant.
+ *   - rgb is dense, planar, row-major: rgb[batch][3][H][W], x (the W index) fastest.
+ *     out is dense: out[batch][H-4][W-4].  out must not overlap rgb.
+ *   - Any pointer alignment natural to the element type and any H, W >= 4 are
+ *     accepted.  The fastest path is taken when W is a multiple of 4 and both base
+ *     pointers are 16-byte aligned (8-byte aligned and even W is next best).
+ *   - The work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and the call returns without waiting for it.
+ *   - The return value is a harris_status.  Nothing is written to stdout/stderr and
+ *     no C++ exception crosses this interface.  On any error nothing is enqueued.
+ *   - batch == 0, H == 4 or W == 4 describe an empty result: HARRIS_OK, no work,
+ *     pointers are not examined.
+ */
+#ifndef HARRIS_H
+#define HARRIS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum harris_status {
+    HARRIS_OK = 0,
+    HARRIS_ERR_NULL = -1,    /* rgb or out is NULL although the result is not empty        */
+    HARRIS_ERR_SHAPE = -2,   /* batch < 0, H < 4, W < 4, or a size overflows 32-bit tiling  */
+    HARRIS_ERR_ARG = -3,     /* k or sobel_scale not finite, unknown dtype/window/tuning    */
+    HARRIS_ERR_LAUNCH = -4   /* the HIP runtime refused the kernel launch                   */
+} harris_status;
+
+/* Element type of the input image. */
+typedef enum harris_dtype {
+    HARRIS_F32 = 0,          /* float32 planes, values used as they are                     */
+    HARRIS_U8 = 1            /* uint8 planes, each value divided by 255 inside the kernel   */
+} harris_dtype;
+
+/* The 3x3 window that accumulates Ixx, Ixy, Iyy. */
+typedef enum harris_window {
+    HARRIS_WINDOW_BOX = 0,      /* unweighted 3x3 sum: the "+3x3" operator of section 4.2      */
+    HARRIS_WINDOW_BINOMIAL = 1  /* [1 2 1; 2 4 2; 1 2 1], the substitute named in chapter 5's
+                                   evaluation (binomial rewrite goal)                         */
+} harris_window;
+
+/*
+ * Optional launch shape, for benchmarking and tests.  Pass NULL (or zero fields)
+ * to let the library choose.  Results never depend on it beyond rounding.
+ *   px            pixels per lane along x: 1, 2, 4 or 8 (must divide W and match the
+ *                 pointer alignment, else HARRIS_ERR_ARG); 0 = widest that fits.
+ *   rows_per_band output rows walked by one wavefront (>= 1); 0 = chosen from the size.
+ *   prefetch      input rows kept in flight per wavefront: 1, 2, 3 or 6; 0 = default.
+ *   waves_per_block  1, 2 or 4 wavefronts per workgroup; 0 = default.
+ *   flags         HARRIS_TUNE_* bits.
+ */
+typedef struct harris_tuning {
+    int px;
+    int rows_per_band;
+    int prefetch;
+    int waves_per_block;
+    unsigned flags;
+} harris_tuning;
+
+#define HARRIS_TUNE_NO_ALTERNATE 1u  /* all bands walk downwards (default: odd bands walk upwards
+                                        so that neighbouring bands read their shared rows together) */
+#define HARRIS_TUNE_NO_XCD_REMAP 2u  /* workgroup i takes tile i (default: tiles are dealt so that
+                                        each of the 8 XCDs gets one contiguous run of tiles)        */
+
+/*
+ * Harris coarsity of float32 images with the integer Sobel matrices
+ * Sx = [-1 0 1; -2 0 2; -1 0 1], Sy = its transpose, and the unweighted 3x3 sum.
+ * (Section 4.2; equals harris_coarsity_ex with HARRIS_F32, sobel_scale 1,
+ * HARRIS_WINDOW_BOX, no tuning.)
+ *   rgb   device, float32 [batch][3][H][W], read only
+ *   k     the coarsity constant kappa (0.04 in the thesis)
+ *   out   device, float32 [batch][H-4][W-4], fully overwritten
+ */
+int harris_coarsity(const float* rgb, int batch, int H, int W, float k, float* out, void* stream);
+
+/* Same for uint8 images; each value is taken as u/255 (stage a0, then section 4.2). */
+int harris_coarsity_u8(const uint8_t* rgb, int batch, int H, int W, float k, float* out, void* stream);
+
+/*
+ * General form.
+ *   rgb          device, element type given by `dtype` (a harris_dtype)
+ *   sobel_scale  factor applied to both Sobel matrices.  1 gives the integer
+ *                matrices; 1.0f/12 gives exactly the operator of the thesis's
+ *                listings (section 4.2), whose results are those of scale 1
+ *                divided by 12^4.
+ *   window       a harris_window
+ *   tuning       NULL, or a launch shape (see harris_tuning)
+ */
+int harris_coarsity_ex(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale,
+                       int window, float* out, const harris_tuning* tuning, void* stream);
+
+/*
+ * The launch shape harris_coarsity_ex would use for this problem (after applying
+ * `tuning`, which may be NULL), written to *chosen; also the number of workgroups
+ * in *n_blocks if n_blocks is not NULL.  rgb_align / out_align are the byte
+ * alignments of the base pointers (pass 16 for ordinary allocations).  Host only;
+ * touches no device.  Returns a harris_status.
+ */
+int harris_plan(int dtype, int batch, int H, int W, int rgb_align, int out_align,
+                const harris_tuning* tuning, harris_tuning* chosen, long long* n_blocks);
+
+/* Static, NUL-terminated description of a harris_status value. */
+const char* harris_strerror(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int harris_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HARRIS_H */

@@ -1,0 +1,12 @@
+"""Harris corner-detection coarsity on AMD MI355X (gfx950).
+
+Thin Python binding over the C interface declared in include/harris.h; every step
+of the computation runs in the library's HIP kernel.  PyTorch only supplies device
+memory and streams.
+"""
+from .binding import (  # noqa: F401
+    HARRIS_F32, HARRIS_U8, HARRIS_WINDOW_BOX, HARRIS_WINDOW_BINOMIAL,
+    HARRIS_TUNE_NO_ALTERNATE, HARRIS_TUNE_NO_XCD_REMAP,
+    HarrisError, HarrisTuning, library_path, load_library,
+    harris_coarsity, harris_coarsity_u8, harris_coarsity_ex, harris_plan, harris_strerror, harris_version,
+)

@@ -1,0 +1,162 @@
+"""ctypes binding of libharris (include/harris.h): argument marshalling only.
+
+The functions have the names and argument order of the C entry points.  Images
+are torch tensors on a ROCm device; their data pointers and the current HIP stream
+are handed to the library unchanged.  There is no fallback: if the shared library
+is missing the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HARRIS_F32, HARRIS_U8 = 0, 1
+HARRIS_WINDOW_BOX, HARRIS_WINDOW_BINOMIAL = 0, 1
+HARRIS_TUNE_NO_ALTERNATE, HARRIS_TUNE_NO_XCD_REMAP = 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libharris.so")
+
+#: every symbol include/harris.h declares
+EXPORTS = ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan",
+           "harris_strerror", "harris_version")
+
+
+class HarrisError(RuntimeError):
+    """A libharris entry point returned a status other than HARRIS_OK."""
+
+    def __init__(self, status: int, message: str):
+        super().__init__("libharris: %s (status %d)" % (message, status))
+        self.status = status
+
+
+class HarrisTuning(ctypes.Structure):
+    """Mirror of `harris_tuning`."""
+    _fields_ = [("px", ctypes.c_int), ("rows_per_band", ctypes.c_int), ("prefetch", ctypes.c_int),
+                ("waves_per_block", ctypes.c_int), ("flags", ctypes.c_uint)]
+
+    def as_dict(self):
+        return {name: int(getattr(self, name)) for name, _ in self._fields_}
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libharris.so from the package directory and declare its prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            "libharris.so is not built (expected at %s). Build it with "
+            "`python -c 'import __graft_entry__ as g; g.build()'` from the repository root. "
+            "There is no CPU fallback." % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    tp = ctypes.POINTER(HarrisTuning)
+    lib.harris_coarsity.argtypes = [vp, ci, ci, ci, cf, vp, vp]
+    lib.harris_coarsity_u8.argtypes = [vp, ci, ci, ci, cf, vp, vp]
+    lib.harris_coarsity_ex.argtypes = [vp, ci, ci, ci, ci, cf, cf, ci, vp, tp, vp]
+    lib.harris_plan.argtypes = [ci, ci, ci, ci, ci, ci, tp, tp, ctypes.POINTER(ctypes.c_longlong)]
+    for name in ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan", "harris_version"):
+        getattr(lib, name).restype = ci
+    lib.harris_strerror.argtypes = [ci]
+    lib.harris_strerror.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def harris_strerror(status: int) -> str:
+    return load_library().harris_strerror(int(status)).decode()
+
+
+def harris_version() -> int:
+    return int(load_library().harris_version())
+
+
+def _check(status: int):
+    if status != 0:
+        raise HarrisError(status, harris_strerror(status))
+
+
+def _tuning_arg(tuning):
+    if tuning is None:
+        return None
+    if isinstance(tuning, HarrisTuning):
+        return ctypes.byref(tuning)
+    return ctypes.byref(HarrisTuning(**tuning))
+
+
+def _prepare(rgb, out, want_dtype):
+    import torch
+    if not isinstance(rgb, torch.Tensor) or rgb.device.type != "cuda":
+        raise TypeError("rgb must be a torch tensor on a ROCm device")
+    if rgb.dtype != want_dtype:
+        raise TypeError("rgb must have dtype %s" % want_dtype)
+    if rgb.dim() != 4 or rgb.shape[1] != 3:
+        raise ValueError("rgb must have shape [batch][3][H][W]")
+    if not rgb.is_contiguous():
+        raise ValueError("rgb must be contiguous (dense planar layout)")
+    B, _, H, W = rgb.shape
+    if H < 4 or W < 4:
+        raise HarrisError(-2, harris_strerror(-2))
+    if out is None:
+        out = torch.empty((B, H - 4, W - 4), dtype=torch.float32, device=rgb.device)
+    else:
+        if (not isinstance(out, torch.Tensor) or out.device != rgb.device or out.dtype != torch.float32
+                or tuple(out.shape) != (B, H - 4, W - 4) or not out.is_contiguous()):
+            raise ValueError("out must be a contiguous float32 tensor [batch][H-4][W-4] on rgb's device")
+    return B, H, W, out
+
+
+def _stream_ptr(stream, device):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(device)
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def harris_coarsity(rgb, k: float = 0.04, out=None, stream=None):
+    """float32 rgb[batch][3][H][W] -> float32 out[batch][H-4][W-4]; integer Sobel, 3x3 sum."""
+    import torch
+    B, H, W, out = _prepare(rgb, out, torch.float32)
+    with torch.cuda.device(rgb.device):
+        _check(load_library().harris_coarsity(rgb.data_ptr(), B, H, W, k, out.data_ptr(), _stream_ptr(stream, rgb.device)))
+    return out
+
+
+def harris_coarsity_u8(rgb, k: float = 0.04, out=None, stream=None):
+    """uint8 rgb[batch][3][H][W] (taken as u/255) -> float32 out[batch][H-4][W-4]."""
+    import torch
+    B, H, W, out = _prepare(rgb, out, torch.uint8)
+    with torch.cuda.device(rgb.device):
+        _check(load_library().harris_coarsity_u8(rgb.data_ptr(), B, H, W, k, out.data_ptr(), _stream_ptr(stream, rgb.device)))
+    return out
+
+
+def harris_coarsity_ex(rgb, k: float = 0.04, sobel_scale: float = 1.0, window: int = HARRIS_WINDOW_BOX,
+                       out=None, tuning=None, stream=None):
+    """General form; the element type is taken from rgb.dtype (float32 or uint8)."""
+    import torch
+    if not isinstance(rgb, torch.Tensor) or rgb.dtype not in (torch.float32, torch.uint8):
+        raise TypeError("rgb must be a float32 or uint8 torch tensor")
+    B, H, W, out = _prepare(rgb, out, rgb.dtype)
+    dtype = HARRIS_U8 if rgb.dtype == torch.uint8 else HARRIS_F32
+    with torch.cuda.device(rgb.device):
+        _check(load_library().harris_coarsity_ex(rgb.data_ptr(), dtype, B, H, W, k, sobel_scale, window,
+                                                 out.data_ptr(), _tuning_arg(tuning), _stream_ptr(stream, rgb.device)))
+    return out
+
+
+def harris_plan(dtype: int, batch: int, H: int, W: int, rgb_align: int = 16, out_align: int = 16, tuning=None):
+    """(launch shape as a dict, number of workgroups) the library would use; host only."""
+    chosen = HarrisTuning()
+    blocks = ctypes.c_longlong(0)
+    _check(load_library().harris_plan(dtype, batch, H, W, rgb_align, out_align, _tuning_arg(tuning),
+                                      ctypes.byref(chosen), ctypes.byref(blocks)))
+    return chosen.as_dict(), int(blocks.value)

@@ -1,0 +1,152 @@
+// C interface of libharris: argument checks, launch-shape planning, dispatch.
+// Everything here runs on the host and touches no device memory.
+
+#include <math.h>
+#include <stdint.h>
+
+#include "harris.h"
+#include "harris_launch.h"
+
+namespace {
+
+constexpr int kVersion = 100;   // 0.1.0
+
+bool power_of_two_aligned(uintptr_t p, unsigned bytes) { return (p & (uintptr_t)(bytes - 1)) == 0; }
+
+int elem_size(int dtype) { return dtype == HARRIS_U8 ? 1 : 4; }
+
+// Can every lane load px input elements and store its result columns with single
+// vector accesses?  Loads are px*elem bytes wide up to 16; stores are min(px,4) floats.
+bool px_fits(int px, int dtype, int W, int rgb_align, int out_align) {
+    if (px < 1 || W % px != 0) return false;
+    int load_bytes = px * elem_size(dtype);
+    if (load_bytes > 16) load_bytes = 16;
+    int store_bytes = (px < 4 ? px : 4) * 4;
+    return rgb_align % load_bytes == 0 && out_align % store_bytes == 0;
+}
+
+int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const harris_tuning* tuning,
+         harris_tuning* chosen, long long* n_blocks, harris_launch::Params* params) {
+    if (dtype != HARRIS_F32 && dtype != HARRIS_U8) return HARRIS_ERR_ARG;
+    if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
+    if (rgb_align < 1 || out_align < 4) return HARRIS_ERR_ARG;
+    harris_tuning t = {0, 0, 0, 0, 0u};
+    if (tuning) t = *tuning;
+    if (t.flags & ~(HARRIS_TUNE_NO_ALTERNATE | HARRIS_TUNE_NO_XCD_REMAP)) return HARRIS_ERR_ARG;
+
+    const int n = H - 4, m = W - 4;
+    if (t.px == 0) {
+        t.px = 1;
+        for (int px = 4; px >= 2; px /= 2)
+            if (px_fits(px, dtype, W, rgb_align, out_align)) { t.px = px; break; }
+    } else if (!((t.px == 1 || t.px == 2 || t.px == 4 || t.px == 8) && px_fits(t.px, dtype, W, rgb_align, out_align))) {
+        return HARRIS_ERR_ARG;
+    }
+    if (t.prefetch == 0) t.prefetch = 3;
+    if (!(t.prefetch == 1 || t.prefetch == 2 || t.prefetch == 3 || t.prefetch == 6)) return HARRIS_ERR_ARG;
+    if (t.waves_per_block == 0) t.waves_per_block = 4;
+    if (!(t.waves_per_block == 1 || t.waves_per_block == 2 || t.waves_per_block == 4)) return HARRIS_ERR_ARG;
+    if (t.rows_per_band < 0) return HARRIS_ERR_ARG;
+
+    const long long pitch = (long long)harris_launch::valid_lanes(t.px) * t.px;
+    const long long n_strips = m > 0 ? (m + pitch - 1) / pitch : 0;
+    if (t.rows_per_band == 0) {
+        // Enough wavefronts to occupy 1024 SIMDs a few times over, but bands no shorter
+        // than 8 rows (each band re-reads 4 rows) and no longer than 64.
+        const long long want_tiles = 4096;
+        long long per_band = (long long)batch * n_strips;
+        long long bands = per_band > 0 ? (want_tiles + per_band - 1) / per_band : 1;
+        long long r = bands > 0 ? n / bands : n;
+        if (r < 8) r = 8;
+        if (r > 64) r = 64;
+        t.rows_per_band = (int)r;
+    }
+    const long long n_bands = n > 0 ? ((long long)n + t.rows_per_band - 1) / t.rows_per_band : 0;
+    const long long tiles_per_image = n_bands * n_strips;
+    const long long n_tiles = tiles_per_image * batch;
+    const long long blocks = (n_tiles + t.waves_per_block - 1) / t.waves_per_block;
+    if (tiles_per_image > 0x7fffffffLL || n_tiles > 0x7fffffffLL) return HARRIS_ERR_SHAPE;
+
+    if (chosen) *chosen = t;
+    if (n_blocks) *n_blocks = blocks;
+    if (params) {
+        params->H = H; params->W = W; params->n = n; params->m = m;
+        params->rows_per_band = t.rows_per_band;
+        params->n_strips = (unsigned)n_strips;
+        params->tiles_per_image = (unsigned)tiles_per_image;
+        params->n_tiles = (unsigned)n_tiles;
+        params->flags = t.flags;
+    }
+    return HARRIS_OK;
+}
+
+unsigned pointer_alignment(const void* p) {
+    uintptr_t v = (uintptr_t)p;
+    unsigned a = 1;
+    while (a < 256 && power_of_two_aligned(v, a * 2)) a *= 2;
+    return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+int harris_plan(int dtype, int batch, int H, int W, int rgb_align, int out_align,
+                const harris_tuning* tuning, harris_tuning* chosen, long long* n_blocks) {
+    return plan(dtype, batch, H, W, rgb_align, out_align, tuning, chosen, n_blocks, nullptr);
+}
+
+int harris_coarsity_ex(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale,
+                       int window, float* out, const harris_tuning* tuning, void* stream) {
+    if (dtype != HARRIS_F32 && dtype != HARRIS_U8) return HARRIS_ERR_ARG;
+    if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
+    if (!isfinite(k) || !isfinite(sobel_scale)) return HARRIS_ERR_ARG;
+    if (window != HARRIS_WINDOW_BOX && window != HARRIS_WINDOW_BINOMIAL) return HARRIS_ERR_ARG;
+    const bool empty = batch == 0 || H == 4 || W == 4;
+    if (!empty && (rgb == nullptr || out == nullptr)) return HARRIS_ERR_NULL;
+    if (!empty && pointer_alignment(out) < 4) return HARRIS_ERR_ARG;
+    if (!empty && dtype == HARRIS_F32 && pointer_alignment(rgb) < 4) return HARRIS_ERR_ARG;
+
+    harris_launch::Params p;
+    harris_tuning shape;
+    long long n_blocks = 0;
+    int rc = plan(dtype, batch, H, W, empty ? 16 : (int)pointer_alignment(rgb), empty ? 16 : (int)pointer_alignment(out),
+                  tuning, &shape, &n_blocks, &p);
+    if (rc != HARRIS_OK) return rc;
+    if (empty) return HARRIS_OK;
+
+    p.rgb = rgb;
+    p.out = out;
+    // The Sobel scale multiplies Ix and Iy, which are linear in gray: fold it (and the
+    // 1/255 of 8-bit input) into the three gray weights.
+    const float in_scale = dtype == HARRIS_U8 ? sobel_scale / 255.0f : sobel_scale;
+    p.wr = 0.299f * in_scale;
+    p.wg = 0.587f * in_scale;
+    p.wb = 0.114f * in_scale;
+    p.k = k;
+    p.wc = window == HARRIS_WINDOW_BINOMIAL ? 2.0f : 1.0f;
+    return harris_launch::launch(p, shape, n_blocks, dtype, stream);
+}
+
+int harris_coarsity(const float* rgb, int batch, int H, int W, float k, float* out, void* stream) {
+    return harris_coarsity_ex(rgb, HARRIS_F32, batch, H, W, k, 1.0f, HARRIS_WINDOW_BOX, out, nullptr, stream);
+}
+
+int harris_coarsity_u8(const uint8_t* rgb, int batch, int H, int W, float k, float* out, void* stream) {
+    return harris_coarsity_ex(rgb, HARRIS_U8, batch, H, W, k, 1.0f, HARRIS_WINDOW_BOX, out, nullptr, stream);
+}
+
+const char* harris_strerror(int status) {
+    switch (status) {
+        case HARRIS_OK: return "success";
+        case HARRIS_ERR_NULL: return "rgb or out is NULL for a non-empty result";
+        case HARRIS_ERR_SHAPE: return "invalid shape: batch < 0, H < 4, W < 4, or too many tiles";
+        case HARRIS_ERR_ARG: return "invalid argument: non-finite k or sobel_scale, misaligned pointer, unknown dtype, window or tuning";
+        case HARRIS_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+        default: return "unknown harris_status";
+    }
+}
+
+int harris_version(void) { return kVersion; }
+
+}  // extern "C"

@@ -1,0 +1,336 @@
+// Fused Harris coarsity kernel for gfx950 (MI355X) and its host-side launcher.
+//
+// One kernel computes every stage of the Harris operator (thesis chapter 4,
+// section 4.2: grayscale, Sobel pair, products, 3x3 window sums, coarsity) and
+// touches device memory only to read the RGB planes once and to write the result
+// once.  The schedule is this library's own; what it keeps from the thesis's
+// section 4.3 is the idea of a pipeline over image lines with separated 3x3
+// kernels and rotating registers, re-cut for a 64-lane wavefront:
+//
+//  * A wavefront owns a vertical strip of the image and walks it row by row.
+//    Lane l holds PX adjacent columns; one row of one plane is a single coalesced
+//    load of 64*PX elements (128 bits per lane for float32 at PX = 4).
+//  * Vertical taps never touch memory: the last two gray rows and the last two
+//    rows of (Ix^2, Ix*Iy, Iy^2) live in registers ("register rotation").  The loop
+//    is unrolled by a multiple of 3, so the rotation is a renaming, not a copy.
+//  * Both 3x3 stages are separated (section 4.3, "Convolution Separation"):
+//    [1 2 1]^T/[-1 0 1]^T down the column from registers first, then the horizontal
+//    taps.  Horizontal neighbours come from the lane to the right through a DPP
+//    wave shift; each stage consumes two columns from the right, so a lane's
+//    output columns start at the lane's own first input column and the result row
+//    is stored with aligned vector stores.
+//  * Wavefronts share nothing (no LDS, no barrier).  The strip of a wavefront
+//    overlaps its right neighbour by the 4-column halo; the last lane(s) only
+//    supply that halo.
+//  * Several input rows per wavefront are kept in flight (a register queue of
+//    D rows), so that memory latency is covered even at one wavefront per SIMD.
+//  * The image is cut into bands of R output rows; a band re-reads the 4 halo
+//    rows of its neighbour.  Odd bands walk upwards, so two neighbouring bands
+//    begin (or end) on the same rows at the same time and the second read hits
+//    in L2; tiles are dealt to workgroups so that each XCD (own L2) gets one
+//    contiguous run of tiles.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <math.h>
+#include <type_traits>
+
+#include "harris.h"
+#include "harris_launch.h"
+
+namespace {
+
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------- small helpers
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+constexpr int gcd_c(int a, int b) { return b == 0 ? a : gcd_c(b, a % b); }
+constexpr int lcm_c(int a, int b) { return a / gcd_c(a, b) * b; }
+
+// Value of v in the lane to the right (lane + 1); lanes without one get 0.
+// DPP control 0x130 is "wave shift left by 1": lane i reads lane i + 1.
+__device__ __forceinline__ float from_right(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, true));
+}
+
+// The two columns to the right of a lane's PX columns: a[PX], a[PX+1].
+template <int PX>
+__device__ __forceinline__ void fetch_halo(float (&a)[PX + 2]) {
+    if constexpr (PX == 1) {
+        a[1] = from_right(a[0]);
+        a[2] = from_right(a[1]);
+    } else {
+        a[PX] = from_right(a[0]);
+        a[PX + 1] = from_right(a[1]);
+    }
+}
+
+// ---------------------------------------------------------------- row loads
+
+// One row segment of the three planes as raw 32-bit words, PX pixels per lane.
+template <typename In, int PX>
+struct RawRow {
+    static constexpr int NW = std::is_same<In, float>::value ? PX : (PX + 3) / 4;
+    uint32_t w[3][NW];
+};
+
+template <typename In, int PX>
+__device__ __forceinline__ void load_row(RawRow<In, PX>& r, const In* __restrict__ row, size_t plane, unsigned col) {
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+        const In* p = row + c * plane + col;
+        if constexpr (std::is_same<In, float>::value) {
+            if constexpr (PX >= 4) {
+#pragma unroll
+                for (int j = 0; j < PX / 4; ++j) {
+                    uint4 v = *reinterpret_cast<const uint4*>(p + 4 * j);
+                    r.w[c][4 * j + 0] = v.x; r.w[c][4 * j + 1] = v.y; r.w[c][4 * j + 2] = v.z; r.w[c][4 * j + 3] = v.w;
+                }
+            } else if constexpr (PX == 2) {
+                uint2 v = *reinterpret_cast<const uint2*>(p);
+                r.w[c][0] = v.x; r.w[c][1] = v.y;
+            } else {
+                r.w[c][0] = *reinterpret_cast<const uint32_t*>(p);
+            }
+        } else {
+            if constexpr (PX >= 16) {
+#pragma unroll
+                for (int j = 0; j < PX / 16; ++j) {
+                    uint4 v = *reinterpret_cast<const uint4*>(p + 16 * j);
+                    r.w[c][4 * j + 0] = v.x; r.w[c][4 * j + 1] = v.y; r.w[c][4 * j + 2] = v.z; r.w[c][4 * j + 3] = v.w;
+                }
+            } else if constexpr (PX == 8) {
+                uint2 v = *reinterpret_cast<const uint2*>(p);
+                r.w[c][0] = v.x; r.w[c][1] = v.y;
+            } else if constexpr (PX == 4) {
+                r.w[c][0] = *reinterpret_cast<const uint32_t*>(p);
+            } else if constexpr (PX == 2) {
+                r.w[c][0] = *reinterpret_cast<const uint16_t*>(p);
+            } else {
+                r.w[c][0] = *p;
+            }
+        }
+    }
+}
+
+// Stage a0 + a1: element i of plane c as float (8-bit values are converted; their
+// 1/255 is folded into the gray weights), then gray = wr*R + wg*G + wb*B.
+template <typename In, int PX>
+__device__ __forceinline__ void gray_row(const RawRow<In, PX>& r, float wr, float wg, float wb, float (&g)[PX]) {
+#pragma unroll
+    for (int i = 0; i < PX; ++i) {
+        float ch[3];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            if constexpr (std::is_same<In, float>::value) ch[c] = __uint_as_float(r.w[c][i]);
+            else ch[c] = (float)((r.w[c][i / 4] >> (8 * (i % 4))) & 0xffu);
+        }
+        g[i] = fmaf(wb, ch[2], fmaf(wg, ch[1], wr * ch[0]));
+    }
+}
+
+// ---------------------------------------------------------------- the pipeline state of one lane
+
+template <int PX>
+struct LineBuffers {
+    float g[3][PX];       // ring of the last three gray rows
+    float p[3][3][PX];    // ring of the last three rows of (Ix*Ix, Ix*Iy, Iy*Iy)
+};
+
+// One row step.  GS is the ring slot that receives this step's gray row.
+// STAGE 0: gray only (first two rows of a band); 1: also Sobel and products (next
+// two rows); 2: also window sums, coarsity and the store of one result row.
+template <int STAGE, int GS, int PX>
+__device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[PX], float wc, float k,
+                                         float* __restrict__ out_row, unsigned col, int m, bool lane_stores) {
+    constexpr int PS = (GS + 1) % 3;          // product slot written at this step
+#pragma unroll
+    for (int i = 0; i < PX; ++i) lb.g[GS][i] = gc[i];
+    if constexpr (STAGE >= 1) {
+        // Stage a2, separated: down the column from the register ring, then along the row.
+        const float (&ga)[PX] = lb.g[(GS + 1) % 3];   // two rows back
+        const float (&gb)[PX] = lb.g[(GS + 2) % 3];   // one row back (the centre row)
+        float vs[PX + 2], vd[PX + 2];
+#pragma unroll
+        for (int i = 0; i < PX; ++i) {
+            vs[i] = fmaf(2.0f, gb[i], ga[i] + gc[i]);  // [1 2 1] down the column
+            vd[i] = gc[i] - ga[i];                     // [-1 0 1] down the column
+        }
+        fetch_halo<PX>(vs);
+        fetch_halo<PX>(vd);
+#pragma unroll
+        for (int i = 0; i < PX; ++i) {
+            float ix = vs[i + 2] - vs[i];                        // [-1 0 1] along the row
+            float iy = fmaf(2.0f, vd[i + 1], vd[i] + vd[i + 2]); // [1 2 1] along the row
+            // Stage a3.
+            lb.p[PS][0][i] = ix * ix;
+            lb.p[PS][1][i] = ix * iy;
+            lb.p[PS][2][i] = iy * iy;
+        }
+    }
+    if constexpr (STAGE >= 2) {
+        // Stage a4, separated: [1 wc 1] down the column, then along the row (wc = 1 for
+        // the unweighted sum, 2 for the binomial window).
+        float s[3][PX];
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+            float v[PX + 2];
+#pragma unroll
+            for (int i = 0; i < PX; ++i)
+                v[i] = fmaf(wc, lb.p[(PS + 2) % 3][q][i], lb.p[(PS + 1) % 3][q][i] + lb.p[PS][q][i]);
+            fetch_halo<PX>(v);
+#pragma unroll
+            for (int i = 0; i < PX; ++i) s[q][i] = fmaf(wc, v[i + 1], v[i] + v[i + 2]);
+        }
+        // Stage a5.
+        float o[PX];
+#pragma unroll
+        for (int i = 0; i < PX; ++i) {
+            float det = fmaf(s[0][i], s[2][i], -(s[1][i] * s[1][i]));
+            float tr = s[0][i] + s[2][i];
+            o[i] = fmaf(-(k * tr), tr, det);
+        }
+        if (out_row != nullptr && lane_stores) {
+            float* dst = out_row + col;
+            if constexpr (PX >= 4) {
+#pragma unroll
+                for (int j = 0; j < PX / 4; ++j)
+                    if ((int)col + 4 * j + 4 <= m)
+                        *reinterpret_cast<float4*>(dst + 4 * j) = make_float4(o[4 * j], o[4 * j + 1], o[4 * j + 2], o[4 * j + 3]);
+            } else if constexpr (PX == 2) {
+                *reinterpret_cast<float2*>(dst) = make_float2(o[0], o[1]);
+            } else {
+                dst[0] = o[0];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- the kernel
+
+// Tiles are numbered image-major, then band, then strip.  Workgroup b of the grid is
+// placed on XCD b % 8 by the hardware dispatcher; this gives XCD x the x-th contiguous
+// run of workgroup-sized tile groups.
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned nb) {
+    const unsigned q = nb / 8, r = nb % 8, x = b % 8, j = b / 8;
+    return x < r ? x * (q + 1) + j : r * (q + 1) + (x - r) * q + j;
+}
+
+template <typename In, int PX, int D>
+__global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::Params p) {
+    constexpr int VL = harris_launch::valid_lanes(PX);
+    constexpr int PITCH = VL * PX;
+    constexpr int U = lcm_c(3, D);            // row steps per loop trip: ring slots stay static
+
+    const unsigned lane = threadIdx.x % kWave;
+    const unsigned wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const unsigned waves_per_block = blockDim.x / kWave;
+    unsigned blk = blockIdx.x;
+    if (!(p.flags & HARRIS_TUNE_NO_XCD_REMAP)) blk = xcd_contiguous(blk, gridDim.x);
+    const unsigned tile = blk * waves_per_block + wave;
+    if (tile >= p.n_tiles) return;            // uniform per wavefront; no barrier is ever used
+
+    const unsigned img = tile / p.tiles_per_image;
+    const unsigned rem = tile % p.tiles_per_image;
+    const int band = (int)(rem / p.n_strips);
+    const int strip = (int)(rem % p.n_strips);
+
+    const int y0 = band * p.rows_per_band;                      // first result row of the band
+    const int rows = min(p.rows_per_band, p.n - y0);            // result rows of this band (>= 1)
+    const int steps = rows + 4;                                 // input rows consumed
+    const bool up = !(p.flags & HARRIS_TUNE_NO_ALTERNATE) && (band & 1);
+
+    const unsigned col = (unsigned)(strip * PITCH) + lane * PX; // first column of this lane (input and result)
+    const unsigned lcol = min(col, (unsigned)(p.W - PX));       // loads stay inside the row
+    const bool lane_stores = lane < (unsigned)VL && (int)col < p.m;
+
+    const size_t plane = (size_t)p.H * p.W;
+    const In* __restrict__ img_in = static_cast<const In*>(p.rgb) + (size_t)img * 3 * plane;
+    float* __restrict__ img_out = p.out + (size_t)img * p.n * p.m;
+
+    // Input row read at step t, kept inside the image for the steps past the band's end.
+    auto in_row = [&](int t) -> int {
+        int r = up ? y0 + rows + 3 - t : y0 + t;
+        return max(0, min(p.H - 1, r));
+    };
+
+    RawRow<In, PX> queue[D];
+    static_for<0, D>([&](auto d) {
+        constexpr int dd = decltype(d)::value;
+        load_row<In, PX>(queue[dd], img_in + (size_t)in_row(dd) * p.W, plane, lcol);
+    });
+
+    LineBuffers<PX> lb;
+    float gc[PX];
+
+    // Rows 0..3 of the band fill the pipeline.
+    static_for<0, 4>([&](auto tt) {
+        constexpr int t = decltype(tt)::value;
+        gray_row<In, PX>(queue[t % D], p.wr, p.wg, p.wb, gc);
+        load_row<In, PX>(queue[t % D], img_in + (size_t)in_row(t + D) * p.W, plane, lcol);
+        row_step<(t < 2 ? 0 : 1), t % 3, PX>(lb, gc, p.wc, p.k, nullptr, col, p.m, false);
+    });
+
+    for (int t0 = 4; t0 < steps; t0 += U) {
+        static_for<0, U>([&](auto uu) {
+            constexpr int u = decltype(uu)::value;
+            const int t = t0 + u;
+            gray_row<In, PX>(queue[(4 + u) % D], p.wr, p.wg, p.wb, gc);
+            load_row<In, PX>(queue[(4 + u) % D], img_in + (size_t)in_row(t + D) * p.W, plane, lcol);
+            // Result row: the top row of the 5-row window that this step completes.
+            const int orow = up ? y0 + rows + 3 - t : y0 + t - 4;
+            float* out_row = t < steps ? img_out + (size_t)orow * p.m : nullptr;
+            row_step<2, (4 + u) % 3, PX>(lb, gc, p.wc, p.k, out_row, col, p.m, lane_stores);
+        });
+    }
+}
+
+template <typename In, int PX, int D>
+hipError_t launch_one(const harris_launch::Params& p, dim3 grid, dim3 block, hipStream_t stream) {
+    hipLaunchKernelGGL((harris_fused_kernel<In, PX, D>), grid, block, 0, stream, p);
+    return hipGetLastError();
+}
+
+template <typename In, int PX>
+hipError_t launch_px(const harris_launch::Params& p, int prefetch, dim3 grid, dim3 block, hipStream_t stream) {
+    switch (prefetch) {
+        case 1: return launch_one<In, PX, 1>(p, grid, block, stream);
+        case 2: return launch_one<In, PX, 2>(p, grid, block, stream);
+        case 3: return launch_one<In, PX, 3>(p, grid, block, stream);
+        case 6: return launch_one<In, PX, 6>(p, grid, block, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <typename In>
+hipError_t launch_in(const harris_launch::Params& p, int px, int prefetch, dim3 grid, dim3 block, hipStream_t stream) {
+    switch (px) {
+        case 1: return launch_px<In, 1>(p, prefetch, grid, block, stream);
+        case 2: return launch_px<In, 2>(p, prefetch, grid, block, stream);
+        case 4: return launch_px<In, 4>(p, prefetch, grid, block, stream);
+        case 8: return launch_px<In, 8>(p, prefetch, grid, block, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+namespace harris_launch {
+
+int launch(const Params& p, const harris_tuning& shape, long long n_blocks, int dtype, void* stream) {
+    const dim3 grid((unsigned)n_blocks), block((unsigned)(shape.waves_per_block * kWave));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = dtype == HARRIS_U8 ? launch_in<uint8_t>(p, shape.px, shape.prefetch, grid, block, s)
+                                      : launch_in<float>(p, shape.px, shape.prefetch, grid, block, s);
+    return e == hipSuccess ? HARRIS_OK : HARRIS_ERR_LAUNCH;
+}
+
+}  // namespace harris_launch

@@ -1,0 +1,35 @@
+// Internal to libharris: what the host-side planner hands to the kernel launcher.
+#ifndef HARRIS_LAUNCH_H
+#define HARRIS_LAUNCH_H
+
+#include "harris.h"
+
+namespace harris_launch {
+
+// Lanes of a 64-lane wavefront that produce result columns when each lane holds px
+// columns: the remaining lane(s) only supply the 4-column halo to the right.
+constexpr int valid_lanes(int px) { return 64 - (4 + px - 1) / px; }
+
+// Kernel arguments (passed by value).
+struct Params {
+    const void* rgb;        // device, [batch][3][H][W]
+    float* out;             // device, [batch][n][m]
+    int H, W;               // input rows, columns
+    int n, m;               // result rows, columns (H-4, W-4)
+    int rows_per_band;      // result rows per band
+    unsigned n_strips;      // strips per band
+    unsigned tiles_per_image;  // n_bands * n_strips
+    unsigned n_tiles;       // batch * tiles_per_image: one wavefront each
+    float wr, wg, wb;       // gray weights, times the Sobel scale (and 1/255 for 8-bit input)
+    float k;                // coarsity constant
+    float wc;               // centre weight of the [1 wc 1] window taps
+    unsigned flags;         // HARRIS_TUNE_* bits
+};
+
+// Enqueue the fused kernel.  `shape` must come from harris_plan (all fields set).
+// Returns a harris_status.
+int launch(const Params& p, const harris_tuning& shape, long long n_blocks, int dtype, void* stream);
+
+}  // namespace harris_launch
+
+#endif

@@ -1,0 +1,108 @@
+"""Host-side checks of libharris that need no GPU: the library loads, exports every
+symbol include/harris.h declares, plans launches sensibly and rejects bad arguments
+before anything is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2212_12035_amd as p
+    if not os.path.exists(p.library_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    p.load_library()
+    return p
+
+
+def test_every_declared_symbol_is_exported(pkg):
+    header = open(os.path.join(ROOT, "include", "harris.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(harris_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(pkg.binding.EXPORTS)
+    lib = ctypes.CDLL(pkg.library_path())
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_strerror(pkg):
+    assert pkg.harris_version() >= 100
+    assert pkg.harris_strerror(0) == "success"
+    msgs = {pkg.harris_strerror(s) for s in (-1, -2, -3, -4)}
+    assert len(msgs) == 4 and all(m and m != "unknown harris_status" for m in msgs)
+    assert pkg.harris_strerror(-99) == "unknown harris_status"
+
+
+def test_plan_picks_widest_vector_path(pkg):
+    shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
+    assert shape["px"] == 4 and blocks > 256 and shape["rows_per_band"] >= 8
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 98)[0]["px"] == 2          # W even, not a multiple of 4
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 97)[0]["px"] == 1          # odd W
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 96, rgb_align=4)[0]["px"] == 1   # misaligned input
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 96, out_align=8)[0]["px"] == 2   # misaligned result
+    assert pkg.harris_plan(pkg.HARRIS_U8, 1, 64, 96, rgb_align=1)[0]["px"] == 1
+    assert pkg.harris_plan(pkg.HARRIS_U8, 1, 8192, 8192)[0]["px"] == 4
+
+
+def test_plan_tile_arithmetic(pkg):
+    # 252 result columns per wavefront at px = 4; 2556 columns -> 11 strips; 1532 rows in
+    # bands of 16 -> 96 bands; 4 wavefronts per workgroup.
+    t = dict(px=4, rows_per_band=16, prefetch=3, waves_per_block=4, flags=0)
+    shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=t)
+    assert shape == t and blocks == (11 * 96 + 3) // 4
+    shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 3, 9, 9, tuning=dict(px=1, rows_per_band=2, prefetch=1, waves_per_block=1, flags=3))
+    assert blocks == 3 * 3 * 1
+    # empty results plan to zero workgroups
+    assert pkg.harris_plan(pkg.HARRIS_F32, 0, 64, 64)[1] == 0
+    assert pkg.harris_plan(pkg.HARRIS_F32, 2, 4, 64)[1] == 0
+    assert pkg.harris_plan(pkg.HARRIS_F32, 2, 64, 4)[1] == 0
+
+
+def test_plan_rejects_bad_arguments(pkg):
+    E = pkg.HarrisError
+    for args, status in [
+        ((7, 1, 64, 64), -3),                       # unknown dtype
+        ((0, -1, 64, 64), -2), ((0, 1, 3, 64), -2), ((0, 1, 64, 3), -2),
+        ((0, 2 ** 31 - 1, 4096, 4096), -2),         # more tiles than a grid can hold
+    ]:
+        with pytest.raises(E) as e:
+            pkg.harris_plan(*args)
+        assert e.value.status == status
+    for bad in (dict(px=3), dict(px=4, prefetch=5), dict(px=4, waves_per_block=3), dict(flags=8), dict(rows_per_band=-1)):
+        with pytest.raises(E) as e:
+            pkg.harris_plan(0, 1, 64, 64, tuning=bad)
+        assert e.value.status == -3
+    with pytest.raises(E):                          # px = 4 needs W % 4 == 0
+        pkg.harris_plan(0, 1, 64, 98, tuning=dict(px=4))
+
+
+def test_entry_points_validate_before_touching_the_device(pkg):
+    # None of these reaches a kernel launch, so they are safe without a GPU.
+    lib = pkg.load_library()
+    nan = float("nan")
+    one = ctypes.c_void_p(4096)
+    assert lib.harris_coarsity(None, 1, 64, 64, 0.04, one, None) == -1
+    assert lib.harris_coarsity(one, 1, 64, 64, 0.04, None, None) == -1
+    assert lib.harris_coarsity(one, 1, 3, 64, 0.04, one, None) == -2
+    assert lib.harris_coarsity(one, -1, 64, 64, 0.04, one, None) == -2
+    assert lib.harris_coarsity(one, 1, 64, 64, nan, one, None) == -3
+    assert lib.harris_coarsity_u8(one, 1, 64, 64, float("inf"), one, None) == -3
+    assert lib.harris_coarsity_ex(one, 0, 1, 64, 64, 0.04, nan, 0, one, None, None) == -3
+    assert lib.harris_coarsity_ex(one, 0, 1, 64, 64, 0.04, 1.0, 2, one, None, None) == -3
+    assert lib.harris_coarsity_ex(one, 5, 1, 64, 64, 0.04, 1.0, 0, one, None, None) == -3
+    assert lib.harris_coarsity_ex(one, 0, 1, 64, 64, 0.04, 1.0, 0, ctypes.c_void_p(4098), None, None) == -3  # out not 4-byte aligned
+    # empty results succeed without looking at the pointers
+    assert lib.harris_coarsity(None, 0, 64, 64, 0.04, None, None) == 0
+    assert lib.harris_coarsity(None, 3, 4, 64, 0.04, None, None) == 0
+    assert lib.harris_coarsity_u8(None, 3, 64, 4, 0.04, None, None) == 0
+
+
+def test_binding_refuses_host_tensors(pkg):
+    import torch
+    with pytest.raises(TypeError):
+        pkg.harris_coarsity(torch.zeros(1, 3, 8, 8))

@@ -1,0 +1,260 @@
+"""GPU parity: libharris (through its C interface) against the CPU oracle, element by
+element on the same seeded inputs.
+
+Bar (float32): max|gpu - oracle| <= 1e-4 * max|oracle| + 1e-6, over the whole result
+and, for batches, per image.  Both sides compute in float32; they differ in summation
+order, in the separated form of the 3x3 kernels and in fused multiply-adds.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+import harris_inputs as hi
+
+pytestmark = pytest.mark.gpu
+
+K = 0.04
+S12 = float(np.float32(1.0) / np.float32(12.0))
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    import paper_2212_12035_amd as pkg
+    if not os.path.exists(pkg.library_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    pkg.load_library()                      # fails loudly if the HIP library is missing
+    return pkg
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def run_gpu(pkg, rgb, **kw):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(rgb)).cuda()
+    out = pkg.harris_coarsity_ex(t, **kw)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def check(got, want, per_image=True):
+    assert got.shape == want.shape and got.dtype == np.float32
+    assert np.all(np.isfinite(got))
+    if want.size == 0:
+        return 0.0
+    bound = 1e-4 * float(np.abs(want).max()) + 1e-6
+    err = float(np.abs(got - want).max())
+    assert err <= bound, "max|gpu-oracle| = %g > %g" % (err, bound)
+    if per_image and want.ndim == 3 and want.shape[0] > 1:
+        for b in range(want.shape[0]):
+            bb = 1e-4 * float(np.abs(want[b]).max()) + 1e-6
+            eb = float(np.abs(got[b] - want[b]).max())
+            assert eb <= bb, "image %d: max|gpu-oracle| = %g > %g" % (b, eb, bb)
+    return err / bound
+
+
+# ---------------------------------------------------------------- the C entry points as they are
+
+def test_tiny_config_default_entry(gpu, oracle):
+    import torch
+    rgb = hi.make("tiny_f32_64x96")
+    say("case tiny_f32_64x96 harris_coarsity")
+    out = gpu.harris_coarsity(torch.from_numpy(rgb).cuda(), K)
+    torch.cuda.synchronize()
+    check(out.cpu().numpy(), oracle.harris(rgb, K))
+
+
+def test_u8_default_entry(gpu, oracle):
+    import torch
+    rgb = hi.make("noise_u8_8192x8192", H=96, W=160)
+    say("case u8 96x160 harris_coarsity_u8")
+    out = gpu.harris_coarsity_u8(torch.from_numpy(rgb).cuda(), K)
+    torch.cuda.synchronize()
+    check(out.cpu().numpy(), oracle.harris(rgb, K))
+
+
+def test_result_buffer_is_fully_overwritten_and_nothing_else(gpu, oracle):
+    import torch
+    rgb = hi.white_noise_f32(40, 2, 37, 264)
+    B, _, H, W = rgb.shape
+    n = B * (H - 4) * (W - 4)
+    say("case guard bands around out, 2x3x37x264")
+    big = torch.full((n + 512,), float("nan"), device="cuda")
+    out = big[256:256 + n].view(B, H - 4, W - 4)
+    gpu.harris_coarsity(torch.from_numpy(rgb).cuda(), K, out=out)
+    torch.cuda.synchronize()
+    host = big.cpu().numpy()
+    assert np.all(np.isnan(host[:256])) and np.all(np.isnan(host[256 + n:]))
+    check(host[256:256 + n].reshape(B, H - 4, W - 4), oracle.harris(rgb, K))
+
+
+# ---------------------------------------------------------------- launch shapes: several tiles, ragged tails
+
+SHAPES = [
+    # (H, W): W picks the widest path; sizes span several strips/bands with ragged ends
+    (23, 520), (41, 1028), (70, 256), (9, 260), (33, 98), (30, 131), (5, 5), (5, 1040), (64, 8), (12, 12),
+]
+
+
+@pytest.mark.parametrize("H,W", SHAPES)
+def test_f32_shapes_default_plan(gpu, oracle, H, W):
+    rgb = hi.white_noise_f32(100 + H + W, 2, H, W)
+    say("case f32 2x3x%dx%d default plan %s" % (H, W, gpu.harris_plan(0, 2, H, W)))
+    check(run_gpu(gpu, rgb, k=K), oracle.harris(rgb, K))
+
+
+@pytest.mark.parametrize("px", [1, 2, 4, 8])
+@pytest.mark.parametrize("prefetch", [1, 2, 3, 6])
+def test_f32_every_kernel_instance(gpu, oracle, px, prefetch):
+    H, W = 45, 8 * 67            # 536 columns: 2-3 strips at px 4/8, 5 at px 2, 9 at px 1
+    rgb = hi.white_noise_f32(7, 2, H, W)
+    want = oracle.harris(rgb, K)
+    for rows, wpb, flags in ((7, 4, 0), (10, 1, 1), (64, 2, 2), (1, 4, 3)):
+        tune = dict(px=px, rows_per_band=rows, prefetch=prefetch, waves_per_block=wpb, flags=flags)
+        say("case f32 2x3x%dx%d %s" % (H, W, tune))
+        check(run_gpu(gpu, rgb, k=K, tuning=tune), want)
+
+
+@pytest.mark.parametrize("px", [1, 2, 4, 8])
+@pytest.mark.parametrize("prefetch", [1, 2, 3, 6])
+def test_u8_every_kernel_instance(gpu, oracle, px, prefetch):
+    H, W = 39, 8 * 65
+    rgb = hi.white_noise_u8(8, 2, H, W)
+    want = oracle.harris(rgb, K)
+    for rows, wpb, flags in ((5, 4, 0), (13, 1, 3)):
+        tune = dict(px=px, rows_per_band=rows, prefetch=prefetch, waves_per_block=wpb, flags=flags)
+        say("case u8 2x3x%dx%d %s" % (H, W, tune))
+        check(run_gpu(gpu, rgb, k=K, tuning=tune), want)
+
+
+def test_misaligned_base_pointers_take_the_narrow_paths(gpu, oracle):
+    import torch
+    H, W = 21, 300
+    rgb = hi.white_noise_f32(9, 1, H, W)
+    want = oracle.harris(rgb, K)
+    flat = torch.zeros(rgb.size + 8, device="cuda")
+    for off in (1, 2, 3):                       # input 4-, 8-, 4-byte aligned only
+        say("case f32 input offset by %d floats" % off)
+        flat[off:off + rgb.size] = torch.from_numpy(rgb.reshape(-1)).cuda()
+        t = flat[off:off + rgb.size].view(1, 3, H, W)
+        out = gpu.harris_coarsity(t, K)
+        torch.cuda.synchronize()
+        check(out.cpu().numpy(), want)
+    oflat = torch.zeros(want.size + 8, device="cuda")
+    src = torch.from_numpy(rgb).cuda()
+    for off in (1, 2):
+        say("case f32 result offset by %d floats" % off)
+        o = oflat[off:off + want.size].view(1, H - 4, W - 4)
+        gpu.harris_coarsity(src, K, out=o)
+        torch.cuda.synchronize()
+        check(o.cpu().numpy(), want)
+    u8 = hi.white_noise_u8(10, 1, H, W)
+    uflat = torch.zeros(u8.size + 8, dtype=torch.uint8, device="cuda")
+    for off in (1, 2):
+        say("case u8 input offset by %d bytes" % off)
+        uflat[off:off + u8.size] = torch.from_numpy(u8.reshape(-1)).cuda()
+        out = gpu.harris_coarsity_u8(uflat[off:off + u8.size].view(1, 3, H, W), K)
+        torch.cuda.synchronize()
+        check(out.cpu().numpy(), oracle.harris(u8, K))
+
+
+# ---------------------------------------------------------------- operator variants
+
+@pytest.mark.parametrize("scale", [1.0, S12])
+@pytest.mark.parametrize("window", [0, 1])
+@pytest.mark.parametrize("k", [0.04, 0.06, 0.0])
+def test_operator_variants(gpu, oracle, scale, window, k):
+    rgb = hi.rectangles_f32(31, 2, 90, 260)
+    say("case variants scale=%g window=%d k=%g" % (scale, window, k))
+    check(run_gpu(gpu, rgb, k=k, sobel_scale=scale, window=window), oracle.harris(rgb, k, scale, window))
+
+
+def test_reduced_workloads_all_recipes(gpu, oracle):
+    for name, kw in [("noise_f32_1536x2560", dict(H=192, W=320)),
+                     ("blobs_f32_2832x4256", dict(H=354, W=532, sigma_lo=3, sigma_hi=25)),
+                     ("rects_f32_64x1080x1920", dict(batch=5, H=135, W=240)),
+                     ("noise_u8_8192x8192", dict(H=256, W=512))]:
+        rgb = hi.make(name, **kw)
+        say("case reduced %s %s" % (name, rgb.shape))
+        check(run_gpu(gpu, rgb, k=K), oracle.harris(rgb, K, nthreads=4))
+
+
+# ---------------------------------------------------------------- degenerate inputs and closed forms on the GPU
+
+def test_constant_image_gives_exact_zero(gpu):
+    rgb = np.empty((1, 3, 40, 300), np.float32)
+    rgb[0, 0], rgb[0, 1], rgb[0, 2] = 0.8125, 0.3, 0.61
+    say("case constant image")
+    assert np.all(run_gpu(gpu, rgb, k=K) == 0.0)
+    u8 = np.full((1, 3, 17, 64), 201, np.uint8)
+    assert np.all(run_gpu(gpu, u8, k=K) == 0.0)
+
+
+def test_horizontal_ramp_closed_form(gpu):
+    a = 2.0 ** -8
+    y, x = np.mgrid[0:20, 0:280]
+    g = (a * x + 0.125).astype(np.float32)
+    rgb = np.ascontiguousarray(np.broadcast_to(g[None, None], (1, 3, 20, 280)))
+    say("case ramp")
+    out = run_gpu(gpu, rgb, k=K)
+    expect = -float(np.float32(K)) * (9.0 * (8 * a) ** 2) ** 2
+    # gray is rounded to f32 before the differences: a few 1e-5 relative on Ix^4
+    assert np.abs(out - expect).max() <= 1e-4 * abs(expect)
+
+
+def test_empty_results(gpu):
+    import torch
+    say("case empty results")
+    assert tuple(gpu.harris_coarsity(torch.zeros(0, 3, 16, 16, device="cuda")).shape) == (0, 12, 12)
+    assert tuple(gpu.harris_coarsity(torch.zeros(2, 3, 4, 16, device="cuda")).shape) == (2, 0, 12)
+    assert tuple(gpu.harris_coarsity_u8(torch.zeros(2, 3, 16, 4, dtype=torch.uint8, device="cuda")).shape) == (2, 12, 0)
+    with pytest.raises(gpu.HarrisError):
+        gpu.harris_coarsity(torch.zeros(1, 3, 3, 16, device="cuda"))
+
+
+def test_runs_on_a_side_stream(gpu, oracle):
+    import torch
+    rgb = hi.white_noise_f32(77, 1, 64, 512)
+    say("case side stream")
+    s = torch.cuda.Stream()
+    t = torch.from_numpy(rgb).cuda()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        out = gpu.harris_coarsity(t, K)
+    s.synchronize()
+    check(out.cpu().numpy(), oracle.harris(rgb, K))
+
+
+# ---------------------------------------------------------------- full sizes, in the launch shape the benchmark times
+
+@pytest.mark.parametrize("name", ["noise_f32_1536x2560", "blobs_f32_2832x4256", "noise_u8_8192x8192"])
+def test_full_size_single_images(gpu, oracle, name):
+    rgb = hi.make(name)
+    say("case full %s %s plan %s" % (name, rgb.shape, gpu.harris_plan(1 if rgb.dtype == np.uint8 else 0, *rgb.shape[:1], *rgb.shape[2:])))
+    got = run_gpu(gpu, rgb, k=K)
+    want = oracle.harris(rgb, K, nthreads=oracle.hardware_threads())
+    say("   ratio to bound: %.3g" % check(got, want))
+
+
+def test_full_size_batch_of_64(gpu, oracle):
+    import torch
+    name = "rects_f32_64x1080x1920"
+    rgb = hi.make(name)
+    say("case full %s %s plan %s" % (name, rgb.shape, gpu.harris_plan(0, 64, 1080, 1920)))
+    got = run_gpu(gpu, rgb, k=K)
+    nt = oracle.hardware_threads()
+    worst = 0.0
+    for b in range(rgb.shape[0]):            # the oracle one image at a time: bounded memory
+        want = oracle.harris(rgb[b], K, nthreads=nt)
+        worst = max(worst, check(got[b], want))
+        assert want.max() > 0                # rectangles have corners: positive responses exist
+        if b % 16 == 15:
+            say("   image %d done" % b)
+    say("   worst ratio to bound: %.3g" % worst)
