@@ -43,7 +43,7 @@ extern "C" {
 typedef enum harris_status {
     HARRIS_OK = 0,
     HARRIS_ERR_NULL = -1,    /* rgb or out is NULL although the result is not empty        */
-    HARRIS_ERR_SHAPE = -2,   /* batch < 0, H < 4, W < 4, or a size overflows 32-bit tiling  */
+    HARRIS_ERR_SHAPE = -2,   /* batch < 0, H < 4, W < 4, W > 2^28, or more than 2^31-1 tiles   */
     HARRIS_ERR_ARG = -3,     /* k or sobel_scale not finite, unknown dtype/window/tuning    */
     HARRIS_ERR_LAUNCH = -4   /* the HIP runtime refused the kernel launch                   */
 } harris_status;

@@ -29,6 +29,7 @@ int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const
          harris_tuning* chosen, long long* n_blocks, harris_launch::Params* params) {
     if (dtype != HARRIS_F32 && dtype != HARRIS_U8) return HARRIS_ERR_ARG;
     if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
+    if (W > (1 << 28)) return HARRIS_ERR_SHAPE;      // byte offsets within a row are 32-bit
     if (rgb_align < 1 || out_align < 4) return HARRIS_ERR_ARG;
     harris_tuning t = {0, 0, 0, 0, 0u};
     if (tuning) t = *tuning;

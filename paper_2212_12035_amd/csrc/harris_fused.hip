@@ -73,7 +73,27 @@ __device__ __forceinline__ void fetch_halo(float (&a)[PX + 2]) {
     }
 }
 
-// ---------------------------------------------------------------- row loads
+// ---------------------------------------------------------------- row loads and stores
+
+// Cache policy of the streaming accesses (the "aux" operand of the buffer
+// instructions): 2 = non-temporal.  Every input row is used by one band (plus the
+// 4 halo rows of its neighbour) and no result is read back, so nothing here
+// should displace other lines from the caches.
+#ifndef HARRIS_LOAD_AUX
+#define HARRIS_LOAD_AUX 2
+#endif
+#ifndef HARRIS_STORE_AUX
+#define HARRIS_STORE_AUX 2
+#endif
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Buffer descriptor over `bytes` bytes at p: raw (unstrided) 32-bit data.  A lane
+// whose byte offset is not below `bytes` loads 0 and stores nothing.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
 
 // One row segment of the three planes as raw 32-bit words, PX pixels per lane.
 template <typename In, int PX>
@@ -82,42 +102,47 @@ struct RawRow {
     uint32_t w[3][NW];
 };
 
+// row points at column 0 of the row in plane 0; voff is the lane's byte offset in the row.
 template <typename In, int PX>
-__device__ __forceinline__ void load_row(RawRow<In, PX>& r, const In* __restrict__ row, size_t plane, unsigned col) {
+__device__ __forceinline__ void load_row(RawRow<In, PX>& r, const In* row, size_t plane, uint32_t row_bytes, uint32_t voff) {
 #pragma unroll
     for (int c = 0; c < 3; ++c) {
-        const In* p = row + c * plane + col;
-        if constexpr (std::is_same<In, float>::value) {
-            if constexpr (PX >= 4) {
+        const __amdgpu_buffer_rsrc_t rs = make_rsrc(row + c * plane, row_bytes);
+        constexpr int BYTES = PX * (int)sizeof(In);
+        if constexpr (BYTES >= 16) {
 #pragma unroll
-                for (int j = 0; j < PX / 4; ++j) {
-                    uint4 v = *reinterpret_cast<const uint4*>(p + 4 * j);
-                    r.w[c][4 * j + 0] = v.x; r.w[c][4 * j + 1] = v.y; r.w[c][4 * j + 2] = v.z; r.w[c][4 * j + 3] = v.w;
-                }
-            } else if constexpr (PX == 2) {
-                uint2 v = *reinterpret_cast<const uint2*>(p);
-                r.w[c][0] = v.x; r.w[c][1] = v.y;
-            } else {
-                r.w[c][0] = *reinterpret_cast<const uint32_t*>(p);
+            for (int j = 0; j < BYTES / 16; ++j) {
+                u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 16 * j, 0, HARRIS_LOAD_AUX);
+                r.w[c][4 * j + 0] = v.x; r.w[c][4 * j + 1] = v.y; r.w[c][4 * j + 2] = v.z; r.w[c][4 * j + 3] = v.w;
             }
+        } else if constexpr (BYTES == 8) {
+            u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, 0, HARRIS_LOAD_AUX);
+            r.w[c][0] = v.x; r.w[c][1] = v.y;
+        } else if constexpr (BYTES == 4) {
+            r.w[c][0] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff, 0, HARRIS_LOAD_AUX);
+        } else if constexpr (BYTES == 2) {
+            r.w[c][0] = __builtin_amdgcn_raw_buffer_load_b16(rs, voff, 0, HARRIS_LOAD_AUX);
         } else {
-            if constexpr (PX >= 16) {
-#pragma unroll
-                for (int j = 0; j < PX / 16; ++j) {
-                    uint4 v = *reinterpret_cast<const uint4*>(p + 16 * j);
-                    r.w[c][4 * j + 0] = v.x; r.w[c][4 * j + 1] = v.y; r.w[c][4 * j + 2] = v.z; r.w[c][4 * j + 3] = v.w;
-                }
-            } else if constexpr (PX == 8) {
-                uint2 v = *reinterpret_cast<const uint2*>(p);
-                r.w[c][0] = v.x; r.w[c][1] = v.y;
-            } else if constexpr (PX == 4) {
-                r.w[c][0] = *reinterpret_cast<const uint32_t*>(p);
-            } else if constexpr (PX == 2) {
-                r.w[c][0] = *reinterpret_cast<const uint16_t*>(p);
-            } else {
-                r.w[c][0] = *p;
-            }
+            r.w[c][0] = __builtin_amdgcn_raw_buffer_load_b8(rs, voff, 0, HARRIS_LOAD_AUX);
         }
+    }
+}
+
+// PX results of one lane to a result row described by rs (its size is the row's
+// bytes, or 0 to store nothing); voff is the lane's byte offset in the row.
+template <int PX>
+__device__ __forceinline__ void store_row(const float (&o)[PX], __amdgpu_buffer_rsrc_t rs, uint32_t voff) {
+    if constexpr (PX >= 4) {
+#pragma unroll
+        for (int j = 0; j < PX / 4; ++j) {
+            u32x4 v = {__float_as_uint(o[4 * j]), __float_as_uint(o[4 * j + 1]), __float_as_uint(o[4 * j + 2]), __float_as_uint(o[4 * j + 3])};
+            __builtin_amdgcn_raw_buffer_store_b128(v, rs, voff + 16 * j, 0, HARRIS_STORE_AUX);
+        }
+    } else if constexpr (PX == 2) {
+        u32x2 v = {__float_as_uint(o[0]), __float_as_uint(o[1])};
+        __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff, 0, HARRIS_STORE_AUX);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[0]), rs, voff, 0, HARRIS_STORE_AUX);
     }
 }
 
@@ -150,7 +175,7 @@ struct LineBuffers {
 // two rows); 2: also window sums, coarsity and the store of one result row.
 template <int STAGE, int GS, int PX>
 __device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[PX], float wc, float k,
-                                         float* __restrict__ out_row, unsigned col, int m, bool lane_stores) {
+                                         __amdgpu_buffer_rsrc_t out_rs, uint32_t store_voff) {
     constexpr int PS = (GS + 1) % 3;          // product slot written at this step
 #pragma unroll
     for (int i = 0; i < PX; ++i) lb.g[GS][i] = gc[i];
@@ -198,19 +223,7 @@ __device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[
             float tr = s[0][i] + s[2][i];
             o[i] = fmaf(-(k * tr), tr, det);
         }
-        if (out_row != nullptr && lane_stores) {
-            float* dst = out_row + col;
-            if constexpr (PX >= 4) {
-#pragma unroll
-                for (int j = 0; j < PX / 4; ++j)
-                    if ((int)col + 4 * j + 4 <= m)
-                        *reinterpret_cast<float4*>(dst + 4 * j) = make_float4(o[4 * j], o[4 * j + 1], o[4 * j + 2], o[4 * j + 3]);
-            } else if constexpr (PX == 2) {
-                *reinterpret_cast<float2*>(dst) = make_float2(o[0], o[1]);
-            } else {
-                dst[0] = o[0];
-            }
-        }
+        store_row<PX>(o, out_rs, store_voff);
     }
 }
 
@@ -250,45 +263,63 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
 
     const unsigned col = (unsigned)(strip * PITCH) + lane * PX; // first column of this lane (input and result)
     const unsigned lcol = min(col, (unsigned)(p.W - PX));       // loads stay inside the row
-    const bool lane_stores = lane < (unsigned)VL && (int)col < p.m;
+    const uint32_t load_voff = lcol * (uint32_t)sizeof(In);
+    // Lanes that only supply halo store nothing: an offset beyond any row.  Lanes whose
+    // columns lie right of the result row are dropped by the buffer's range check.
+    const uint32_t store_voff = lane < (unsigned)VL ? col * 4u : 0x80000000u;
+    const uint32_t in_row_bytes = (uint32_t)p.W * (uint32_t)sizeof(In);
+    const uint32_t out_row_bytes = (uint32_t)p.m * 4u;
 
     const size_t plane = (size_t)p.H * p.W;
-    const In* __restrict__ img_in = static_cast<const In*>(p.rgb) + (size_t)img * 3 * plane;
-    float* __restrict__ img_out = p.out + (size_t)img * p.n * p.m;
+    const In* img_in = static_cast<const In*>(p.rgb) + (size_t)img * 3 * plane;
+    float* img_out = p.out + (size_t)img * p.n * p.m;
 
-    // Input row read at step t, kept inside the image for the steps past the band's end.
-    auto in_row = [&](int t) -> int {
+    // Input row read at step t.  Steps past the band's end (the loop runs in trips of U
+    // steps, and the queue reads D rows ahead) get an empty descriptor: such a load
+    // returns zeros and moves no data.
+    auto in_row_ptr = [&](int t) -> const In* {
         int r = up ? y0 + rows + 3 - t : y0 + t;
-        return max(0, min(p.H - 1, r));
+        r = max(0, min(p.H - 1, r));
+        return img_in + (size_t)r * p.W;
     };
+    auto in_row_size = [&](int t) -> uint32_t { return t < steps ? in_row_bytes : 0u; };
 
     RawRow<In, PX> queue[D];
     static_for<0, D>([&](auto d) {
         constexpr int dd = decltype(d)::value;
-        load_row<In, PX>(queue[dd], img_in + (size_t)in_row(dd) * p.W, plane, lcol);
+        load_row<In, PX>(queue[dd], in_row_ptr(dd), plane, in_row_size(dd), load_voff);
+        __builtin_amdgcn_sched_barrier(0);
     });
 
     LineBuffers<PX> lb;
     float gc[PX];
+    const __amdgpu_buffer_rsrc_t no_store = make_rsrc(img_out, 0);
 
     // Rows 0..3 of the band fill the pipeline.
     static_for<0, 4>([&](auto tt) {
         constexpr int t = decltype(tt)::value;
         gray_row<In, PX>(queue[t % D], p.wr, p.wg, p.wb, gc);
-        load_row<In, PX>(queue[t % D], img_in + (size_t)in_row(t + D) * p.W, plane, lcol);
-        row_step<(t < 2 ? 0 : 1), t % 3, PX>(lb, gc, p.wc, p.k, nullptr, col, p.m, false);
+        __builtin_amdgcn_sched_barrier(0);
+        load_row<In, PX>(queue[t % D], in_row_ptr(t + D), plane, in_row_size(t + D), load_voff);
+        __builtin_amdgcn_sched_barrier(0);
+        row_step<(t < 2 ? 0 : 1), t % 3, PX>(lb, gc, p.wc, p.k, no_store, store_voff);
     });
 
     for (int t0 = 4; t0 < steps; t0 += U) {
         static_for<0, U>([&](auto uu) {
             constexpr int u = decltype(uu)::value;
             const int t = t0 + u;
+            // The slot's registers are free as soon as its gray row exists: refill it at
+            // once, so that D rows stay in flight while the rest of the step computes.
             gray_row<In, PX>(queue[(4 + u) % D], p.wr, p.wg, p.wb, gc);
-            load_row<In, PX>(queue[(4 + u) % D], img_in + (size_t)in_row(t + D) * p.W, plane, lcol);
-            // Result row: the top row of the 5-row window that this step completes.
-            const int orow = up ? y0 + rows + 3 - t : y0 + t - 4;
-            float* out_row = t < steps ? img_out + (size_t)orow * p.m : nullptr;
-            row_step<2, (4 + u) % 3, PX>(lb, gc, p.wc, p.k, out_row, col, p.m, lane_stores);
+            __builtin_amdgcn_sched_barrier(0);
+            load_row<In, PX>(queue[(4 + u) % D], in_row_ptr(t + D), plane, in_row_size(t + D), load_voff);
+            __builtin_amdgcn_sched_barrier(0);
+            // Result row: the top row of the 5-row window that this step completes.  Steps
+            // past the band's end get an empty descriptor and store nothing.
+            const int orow = max(0, min(p.n - 1, up ? y0 + rows + 3 - t : y0 + t - 4));
+            const __amdgpu_buffer_rsrc_t out_rs = make_rsrc(img_out + (size_t)orow * p.m, t < steps ? out_row_bytes : 0u);
+            row_step<2, (4 + u) % 3, PX>(lb, gc, p.wc, p.k, out_rs, store_voff);
         });
     }
 }
