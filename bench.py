@@ -36,8 +36,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=72)
     ap.add_argument("--workload", default=WORKLOAD, help="one of harris_inputs.WORKLOADS (default: the headline one)")
     ap.add_argument("--rotate-bytes", type=float, default=float(1 << 30), help="distinct buffer bytes to rotate over")
+    ap.add_argument("--schedule", type=int, default=0, help="0 auto, 1 bands, 2 tiles")
     ap.add_argument("--px", type=int, default=0)
-    ap.add_argument("--rows-per-band", type=int, default=0)
+    ap.add_argument("--rows", type=int, default=0)
     ap.add_argument("--prefetch", type=int, default=0)
     ap.add_argument("--waves-per-block", type=int, default=0)
     ap.add_argument("--flags", type=int, default=0)
@@ -81,7 +82,7 @@ def main():
     ins = [base] + [torch.roll(base, shifts=i, dims=2) for i in range(1, n_pairs)]
     outs = [torch.empty((B, n, m), dtype=torch.float32, device=dev) for _ in range(n_pairs)]
 
-    tuning = pkg.HarrisTuning(args.px, args.rows_per_band, args.prefetch, args.waves_per_block, args.flags)
+    tuning = pkg.HarrisTuning(args.schedule, args.px, args.rows, args.prefetch, args.waves_per_block, args.flags)
     shape, n_blocks = pkg.harris_plan(pkg.HARRIS_U8 if is_u8 else pkg.HARRIS_F32, B, H, W, tuning=tuning)
     stream = torch.cuda.current_stream(dev)
     sptr = ctypes.c_void_p(stream.cuda_stream)

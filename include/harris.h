@@ -64,25 +64,41 @@ typedef enum harris_window {
 /*
  * Optional launch shape, for benchmarking and tests.  Pass NULL (or zero fields)
  * to let the library choose.  Results never depend on it beyond rounding.
- *   px            pixels per lane along x: 1, 2, 4 or 8 (must divide W and match the
- *                 pointer alignment, else HARRIS_ERR_ARG); 0 = widest that fits.
- *   rows_per_band output rows walked by one wavefront (>= 1); 0 = chosen from the size.
- *   prefetch      input rows kept in flight per wavefront: 1, 2, 3 or 6; 0 = default.
- *   waves_per_block  1, 2 or 4 wavefronts per workgroup; 0 = default.
- *   flags         HARRIS_TUNE_* bits.
+ *
+ *   schedule  HARRIS_SCHEDULE_BANDS: one wavefront walks a band of `rows` result rows of
+ *             one strip from top to bottom (or bottom to top), with `prefetch` input rows
+ *             in flight.  HARRIS_SCHEDULE_TILES: a workgroup of `waves_per_block`
+ *             wavefronts loads a tile of waves_per_block * rows input rows at once and
+ *             hands the gray rows that two wavefronts share through LDS.  0 = chosen
+ *             from the size.
+ *   px        pixels per lane along x: 1, 2, 4 or (BANDS only) 8; must divide W and match
+ *             the pointer alignment, else HARRIS_ERR_ARG; 0 = widest of 1, 2, 4 that fits.
+ *   rows      BANDS: result rows per band (>= 1).  TILES: input rows per wavefront, 4 or
+ *             8.  0 = chosen from the size.
+ *   prefetch  BANDS only: input rows kept in flight per wavefront, 1, 2, 3 or 6; 0 = default.
+ *   waves_per_block  BANDS: 1, 2 or 4.  TILES: 2 to 16.  0 = default.
+ *   flags     HARRIS_TUNE_* bits.
  */
 typedef struct harris_tuning {
+    int schedule;
     int px;
-    int rows_per_band;
+    int rows;
     int prefetch;
     int waves_per_block;
     unsigned flags;
 } harris_tuning;
 
-#define HARRIS_TUNE_NO_ALTERNATE 1u  /* all bands walk downwards (default: odd bands walk upwards
-                                        so that neighbouring bands read their shared rows together) */
-#define HARRIS_TUNE_NO_XCD_REMAP 2u  /* workgroup i takes tile i (default: tiles are dealt so that
-                                        each of the 8 XCDs gets one contiguous run of tiles)        */
+#define HARRIS_SCHEDULE_BANDS 1
+#define HARRIS_SCHEDULE_TILES 2
+
+#define HARRIS_TUNE_NO_ALTERNATE 1u  /* BANDS: all bands walk downwards (default: odd bands walk
+                                        upwards, so that neighbouring bands read their shared rows
+                                        at the same time)                                            */
+#define HARRIS_TUNE_NO_XCD_REMAP 2u  /* workgroup i takes tile group i (default: tiles are dealt so
+                                        that each of the 8 XCDs gets one contiguous run of tiles)   */
+#define HARRIS_TUNE_CACHED_LOADS 4u  /* load input rows with the default cache policy             */
+#define HARRIS_TUNE_STREAM_LOADS 8u  /* load input rows non-temporal.  With neither bit the library
+                                        decides from the size of the problem                        */
 
 /*
  * Harris coarsity of float32 images with the integer Sobel matrices

@@ -12,7 +12,8 @@ import os
 
 HARRIS_F32, HARRIS_U8 = 0, 1
 HARRIS_WINDOW_BOX, HARRIS_WINDOW_BINOMIAL = 0, 1
-HARRIS_TUNE_NO_ALTERNATE, HARRIS_TUNE_NO_XCD_REMAP = 1, 2
+HARRIS_SCHEDULE_BANDS, HARRIS_SCHEDULE_TILES = 1, 2
+HARRIS_TUNE_NO_ALTERNATE, HARRIS_TUNE_NO_XCD_REMAP, HARRIS_TUNE_CACHED_LOADS, HARRIS_TUNE_STREAM_LOADS = 1, 2, 4, 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libharris.so")
@@ -32,7 +33,7 @@ class HarrisError(RuntimeError):
 
 class HarrisTuning(ctypes.Structure):
     """Mirror of `harris_tuning`."""
-    _fields_ = [("px", ctypes.c_int), ("rows_per_band", ctypes.c_int), ("prefetch", ctypes.c_int),
+    _fields_ = [("schedule", ctypes.c_int), ("px", ctypes.c_int), ("rows", ctypes.c_int), ("prefetch", ctypes.c_int),
                 ("waves_per_block", ctypes.c_int), ("flags", ctypes.c_uint)]
 
     def as_dict(self):

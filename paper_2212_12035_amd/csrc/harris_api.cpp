@@ -31,9 +31,11 @@ int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const
     if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
     if (W > (1 << 28)) return HARRIS_ERR_SHAPE;      // byte offsets within a row are 32-bit
     if (rgb_align < 1 || out_align < 4) return HARRIS_ERR_ARG;
-    harris_tuning t = {0, 0, 0, 0, 0u};
+    harris_tuning t = {0, 0, 0, 0, 0, 0u};
     if (tuning) t = *tuning;
-    if (t.flags & ~(HARRIS_TUNE_NO_ALTERNATE | HARRIS_TUNE_NO_XCD_REMAP)) return HARRIS_ERR_ARG;
+    if (t.flags & ~(HARRIS_TUNE_NO_ALTERNATE | HARRIS_TUNE_NO_XCD_REMAP | HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS)) return HARRIS_ERR_ARG;
+    if ((t.flags & HARRIS_TUNE_CACHED_LOADS) && (t.flags & HARRIS_TUNE_STREAM_LOADS)) return HARRIS_ERR_ARG;
+    if (t.schedule != 0 && t.schedule != HARRIS_SCHEDULE_BANDS && t.schedule != HARRIS_SCHEDULE_TILES) return HARRIS_ERR_ARG;
 
     const int n = H - 4, m = W - 4;
     if (t.px == 0) {
@@ -43,36 +45,68 @@ int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const
     } else if (!((t.px == 1 || t.px == 2 || t.px == 4 || t.px == 8) && px_fits(t.px, dtype, W, rgb_align, out_align))) {
         return HARRIS_ERR_ARG;
     }
-    if (t.prefetch == 0) t.prefetch = 3;
-    if (!(t.prefetch == 1 || t.prefetch == 2 || t.prefetch == 3 || t.prefetch == 6)) return HARRIS_ERR_ARG;
-    if (t.waves_per_block == 0) t.waves_per_block = 4;
-    if (!(t.waves_per_block == 1 || t.waves_per_block == 2 || t.waves_per_block == 4)) return HARRIS_ERR_ARG;
-    if (t.rows_per_band < 0) return HARRIS_ERR_ARG;
-
+    if (t.rows < 0 || t.prefetch < 0 || t.waves_per_block < 0) return HARRIS_ERR_ARG;
     const long long pitch = (long long)harris_launch::valid_lanes(t.px) * t.px;
     const long long n_strips = m > 0 ? (m + pitch - 1) / pitch : 0;
-    if (t.rows_per_band == 0) {
-        // Enough wavefronts to occupy 1024 SIMDs a few times over, but bands no shorter
-        // than 8 rows (each band re-reads 4 rows) and no longer than 64.
-        const long long want_tiles = 4096;
-        long long per_band = (long long)batch * n_strips;
-        long long bands = per_band > 0 ? (want_tiles + per_band - 1) / per_band : 1;
-        long long r = bands > 0 ? n / bands : n;
-        if (r < 8) r = 8;
-        if (r > 64) r = 64;
-        t.rows_per_band = (int)r;
+
+    if (t.schedule == 0) t.schedule = HARRIS_SCHEDULE_BANDS;
+
+    // Bytes the launch moves; against the 256 MB last-level cache this decides the load policy
+    // and whether there is enough work for four-wavefront workgroups.
+    const long long elem = elem_size(dtype);
+    const long long footprint = (long long)batch * (3LL * H * W * elem + 4LL * n * m);
+    const bool large = footprint > (256LL << 20);
+    if (!(t.flags & (HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS)))
+        t.flags |= large ? HARRIS_TUNE_CACHED_LOADS : HARRIS_TUNE_STREAM_LOADS;
+
+    long long tile_rows;       // result rows per band or tile
+    if (t.schedule == HARRIS_SCHEDULE_TILES) {
+        if (t.rows == 0) t.rows = 4;
+        if (t.waves_per_block == 0) t.waves_per_block = 4;
+        if (!(t.rows == 4 || t.rows == 8) || t.waves_per_block < 2 || t.waves_per_block > 16) return HARRIS_ERR_ARG;
+        if (t.prefetch != 0) return HARRIS_ERR_ARG;
+        if (t.px > 4) return HARRIS_ERR_ARG;                           // 8 rows of 8 pixels per lane do not fit the registers
+        tile_rows = (long long)t.rows * t.waves_per_block - 4;
+    } else {
+        if (t.prefetch == 0) t.prefetch = large ? 6 : 3;
+        if (!(t.prefetch == 1 || t.prefetch == 2 || t.prefetch == 3 || t.prefetch == 6)) return HARRIS_ERR_ARG;
+        if (t.waves_per_block == 0) t.waves_per_block = large ? 4 : 1;
+        if (!(t.waves_per_block == 1 || t.waves_per_block == 2 || t.waves_per_block == 4)) return HARRIS_ERR_ARG;
+        if (t.rows == 0) {
+            if (large) {
+                t.rows = 32;       // thousands of bands in any case: measured best trade of halo rows against run length
+            } else {
+                // Everything is resident at once: the launch ends when the busiest of the 256
+                // CUs ends.  A CU holding w wavefronts of r+4 row steps each needs about
+                // w*(r+4) step times, so take the band height r in 16..64 that minimises
+                // ceil(bands*strips/256) * (r+4), with at least 3 wavefronts per CU to keep
+                // its memory pipeline fed (ties: the taller band, which re-reads less).
+                const long long per_band = (long long)batch * n_strips;
+                long long best_r = 16, best_cost = -1;
+                for (long long r = 16; r <= 64; ++r) {
+                    const long long waves = ((n + r - 1) / r) * per_band;
+                    const long long per_cu = (waves + 255) / 256;
+                    if (per_cu < 3 && r > 16) break;
+                    const long long cost = per_cu * (r + 4);
+                    if (best_cost < 0 || cost <= best_cost) { best_cost = cost; best_r = r; }
+                }
+                t.rows = (int)best_r;
+            }
+        }
+        tile_rows = t.rows;
     }
-    const long long n_bands = n > 0 ? ((long long)n + t.rows_per_band - 1) / t.rows_per_band : 0;
+    const long long n_bands = n > 0 ? ((long long)n + tile_rows - 1) / tile_rows : 0;
     const long long tiles_per_image = n_bands * n_strips;
     const long long n_tiles = tiles_per_image * batch;
-    const long long blocks = (n_tiles + t.waves_per_block - 1) / t.waves_per_block;
+    // BANDS: one wavefront per tile; TILES: one workgroup per tile.
+    const long long blocks = t.schedule == HARRIS_SCHEDULE_TILES ? n_tiles : (n_tiles + t.waves_per_block - 1) / t.waves_per_block;
     if (tiles_per_image > 0x7fffffffLL || n_tiles > 0x7fffffffLL) return HARRIS_ERR_SHAPE;
 
     if (chosen) *chosen = t;
     if (n_blocks) *n_blocks = blocks;
     if (params) {
         params->H = H; params->W = W; params->n = n; params->m = m;
-        params->rows_per_band = t.rows_per_band;
+        params->rows_per_band = (int)tile_rows;
         params->n_strips = (unsigned)n_strips;
         params->tiles_per_image = (unsigned)tiles_per_image;
         params->n_tiles = (unsigned)n_tiles;

@@ -75,15 +75,17 @@ __device__ __forceinline__ void fetch_halo(float (&a)[PX + 2]) {
 
 // ---------------------------------------------------------------- row loads and stores
 
-// Cache policy of the streaming accesses (the "aux" operand of the buffer
-// instructions): 2 = non-temporal.  Every input row is used by one band (plus the
-// 4 halo rows of its neighbour) and no result is read back, so nothing here
-// should displace other lines from the caches.
-#ifndef HARRIS_LOAD_AUX
-#define HARRIS_LOAD_AUX 2
-#endif
+// Cache policy of the accesses (the "aux" operand of the buffer instructions):
+// 0 = default, 2 = non-temporal.  Results are never read back, so they are always
+// stored non-temporal.  Input rows are loaded non-temporal when the whole problem
+// fits the last-level cache anyway, and with the default policy otherwise: then
+// the line that two neighbouring strips share, and the rows that two neighbouring
+// bands share, are found in the CU's vector cache by the second wavefront of the
+// same workgroup.
+constexpr int kAuxDefault = 0;
+constexpr int kAuxNonTemporal = 2;
 #ifndef HARRIS_STORE_AUX
-#define HARRIS_STORE_AUX 2
+#define HARRIS_STORE_AUX kAuxNonTemporal
 #endif
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -103,7 +105,7 @@ struct RawRow {
 };
 
 // row points at column 0 of the row in plane 0; voff is the lane's byte offset in the row.
-template <typename In, int PX>
+template <typename In, int PX, int AUX>
 __device__ __forceinline__ void load_row(RawRow<In, PX>& r, const In* row, size_t plane, uint32_t row_bytes, uint32_t voff) {
 #pragma unroll
     for (int c = 0; c < 3; ++c) {
@@ -112,18 +114,18 @@ __device__ __forceinline__ void load_row(RawRow<In, PX>& r, const In* row, size_
         if constexpr (BYTES >= 16) {
 #pragma unroll
             for (int j = 0; j < BYTES / 16; ++j) {
-                u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 16 * j, 0, HARRIS_LOAD_AUX);
+                u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 16 * j, 0, AUX);
                 r.w[c][4 * j + 0] = v.x; r.w[c][4 * j + 1] = v.y; r.w[c][4 * j + 2] = v.z; r.w[c][4 * j + 3] = v.w;
             }
         } else if constexpr (BYTES == 8) {
-            u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, 0, HARRIS_LOAD_AUX);
+            u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, 0, AUX);
             r.w[c][0] = v.x; r.w[c][1] = v.y;
         } else if constexpr (BYTES == 4) {
-            r.w[c][0] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff, 0, HARRIS_LOAD_AUX);
+            r.w[c][0] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff, 0, AUX);
         } else if constexpr (BYTES == 2) {
-            r.w[c][0] = __builtin_amdgcn_raw_buffer_load_b16(rs, voff, 0, HARRIS_LOAD_AUX);
+            r.w[c][0] = __builtin_amdgcn_raw_buffer_load_b16(rs, voff, 0, AUX);
         } else {
-            r.w[c][0] = __builtin_amdgcn_raw_buffer_load_b8(rs, voff, 0, HARRIS_LOAD_AUX);
+            r.w[c][0] = __builtin_amdgcn_raw_buffer_load_b8(rs, voff, 0, AUX);
         }
     }
 }
@@ -237,7 +239,7 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned nb) {
     return x < r ? x * (q + 1) + j : r * (q + 1) + (x - r) * q + j;
 }
 
-template <typename In, int PX, int D>
+template <typename In, int PX, int D, int LAUX>
 __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::Params p) {
     constexpr int VL = harris_launch::valid_lanes(PX);
     constexpr int PITCH = VL * PX;
@@ -287,7 +289,7 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
     RawRow<In, PX> queue[D];
     static_for<0, D>([&](auto d) {
         constexpr int dd = decltype(d)::value;
-        load_row<In, PX>(queue[dd], in_row_ptr(dd), plane, in_row_size(dd), load_voff);
+        load_row<In, PX, LAUX>(queue[dd], in_row_ptr(dd), plane, in_row_size(dd), load_voff);
         __builtin_amdgcn_sched_barrier(0);
     });
 
@@ -300,7 +302,7 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
         constexpr int t = decltype(tt)::value;
         gray_row<In, PX>(queue[t % D], p.wr, p.wg, p.wb, gc);
         __builtin_amdgcn_sched_barrier(0);
-        load_row<In, PX>(queue[t % D], in_row_ptr(t + D), plane, in_row_size(t + D), load_voff);
+        load_row<In, PX, LAUX>(queue[t % D], in_row_ptr(t + D), plane, in_row_size(t + D), load_voff);
         __builtin_amdgcn_sched_barrier(0);
         row_step<(t < 2 ? 0 : 1), t % 3, PX>(lb, gc, p.wc, p.k, no_store, store_voff);
     });
@@ -313,7 +315,7 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
             // once, so that D rows stay in flight while the rest of the step computes.
             gray_row<In, PX>(queue[(4 + u) % D], p.wr, p.wg, p.wb, gc);
             __builtin_amdgcn_sched_barrier(0);
-            load_row<In, PX>(queue[(4 + u) % D], in_row_ptr(t + D), plane, in_row_size(t + D), load_voff);
+            load_row<In, PX, LAUX>(queue[(4 + u) % D], in_row_ptr(t + D), plane, in_row_size(t + D), load_voff);
             __builtin_amdgcn_sched_barrier(0);
             // Result row: the top row of the 5-row window that this step completes.  Steps
             // past the band's end get an empty descriptor and store nothing.
@@ -324,30 +326,139 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
     }
 }
 
+
+// ---------------------------------------------------------------- the tile kernel
+//
+// Second schedule, for images too small to keep long-lived wavefronts busy: a
+// workgroup of NW wavefronts owns a tile of NW*RW input rows of one strip, and every
+// wavefront requests its RW rows (3*RW loads) at once, so no wavefront goes through a
+// chain of dependent memory round trips.  Wavefront w turns its rows into gray,
+// publishes its first four gray rows in LDS and, after one barrier, takes the four
+// gray rows below its own from wavefront w+1 there: nothing is read twice inside a
+// tile.  Each wavefront then runs the same register pipeline as the band kernel over
+// its RW+4 gray rows and stores RW result rows (the last wavefront has no neighbour
+// below and stores RW-4).  A tile yields NW*RW-4 result rows; the tile below re-reads
+// four rows.
+template <typename In, int PX, int RW, int LAUX>
+__global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::Params p) {
+    constexpr int VL = harris_launch::valid_lanes(PX);
+    constexpr int PITCH = VL * PX;
+    extern __shared__ __align__(16) float halo_lds[];           // [NW][4][64][PX]
+
+    const unsigned lane = threadIdx.x % kWave;
+    const unsigned wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const unsigned n_waves = blockDim.x / kWave;
+    unsigned tile = blockIdx.x;
+    if (!(p.flags & HARRIS_TUNE_NO_XCD_REMAP)) tile = xcd_contiguous(tile, gridDim.x);
+    // gridDim.x == n_tiles: every workgroup has a tile and every wavefront reaches the barrier.
+
+    const unsigned img = tile / p.tiles_per_image;
+    const unsigned rem = tile % p.tiles_per_image;
+    const int band = (int)(rem / p.n_strips);
+    const int strip = (int)(rem % p.n_strips);
+
+    const int tile_rows = p.rows_per_band;                      // result rows per tile: NW*RW - 4
+    const int y_wave = band * tile_rows + (int)wave * RW;       // first input row = first result row of this wavefront
+    const int y_end = min(p.n, (band + 1) * tile_rows);         // result rows of this tile end here
+    const int out_rows = max(0, min(RW, y_end - y_wave));       // result rows this wavefront stores
+
+    const unsigned col = (unsigned)(strip * PITCH) + lane * PX;
+    const unsigned lcol = min(col, (unsigned)(p.W - PX));
+    const uint32_t load_voff = lcol * (uint32_t)sizeof(In);
+    const uint32_t store_voff = lane < (unsigned)VL ? col * 4u : 0x80000000u;
+    const uint32_t in_row_bytes = (uint32_t)p.W * (uint32_t)sizeof(In);
+    const uint32_t out_row_bytes = (uint32_t)p.m * 4u;
+
+    const size_t plane = (size_t)p.H * p.W;
+    const In* img_in = static_cast<const In*>(p.rgb) + (size_t)img * 3 * plane;
+    float* img_out = p.out + (size_t)img * p.n * p.m;
+
+    // All RW rows of this wavefront at once; rows below the image get an empty descriptor.
+    RawRow<In, PX> raw[RW];
+    static_for<0, RW>([&](auto tt) {
+        constexpr int t = decltype(tt)::value;
+        const int r = y_wave + t;
+        load_row<In, PX, LAUX>(raw[t], img_in + (size_t)min(r, p.H - 1) * p.W, plane, r < p.H ? in_row_bytes : 0u, load_voff);
+    });
+    __builtin_amdgcn_sched_barrier(0);
+
+    LineBuffers<PX> lb;
+    float gc[PX];
+    float* my_halo = halo_lds + ((size_t)wave * 4 * kWave + lane) * PX;
+    auto out_desc = [&](int t) {   // result row completed by step t (t >= 4)
+        const int orow = min(p.n - 1, y_wave + t - 4);
+        return make_rsrc(img_out + (size_t)orow * p.m, t - 4 < out_rows ? out_row_bytes : 0u);
+    };
+    const __amdgpu_buffer_rsrc_t no_store = make_rsrc(img_out, 0);
+
+    static_for<0, RW>([&](auto tt) {
+        constexpr int t = decltype(tt)::value;
+        gray_row<In, PX>(raw[t], p.wr, p.wg, p.wb, gc);
+        if constexpr (t < 4) {
+#pragma unroll
+            for (int i = 0; i < PX; ++i) my_halo[(size_t)t * kWave * PX + i] = gc[i];
+        }
+        if constexpr (t < 4) row_step<(t < 2 ? 0 : 1), t % 3, PX>(lb, gc, p.wc, p.k, no_store, store_voff);
+        else row_step<2, t % 3, PX>(lb, gc, p.wc, p.k, out_desc(t), store_voff);
+    });
+
+    __syncthreads();
+
+    if (wave + 1 < n_waves) {
+        const float* below = halo_lds + ((size_t)(wave + 1) * 4 * kWave + lane) * PX;
+        static_for<RW, RW + 4>([&](auto tt) {
+            constexpr int t = decltype(tt)::value;
+#pragma unroll
+            for (int i = 0; i < PX; ++i) gc[i] = below[(size_t)(t - RW) * kWave * PX + i];
+            row_step<2, t % 3, PX>(lb, gc, p.wc, p.k, out_desc(t), store_voff);
+        });
+    }
+}
+
 template <typename In, int PX, int D>
-hipError_t launch_one(const harris_launch::Params& p, dim3 grid, dim3 block, hipStream_t stream) {
-    hipLaunchKernelGGL((harris_fused_kernel<In, PX, D>), grid, block, 0, stream, p);
+hipError_t launch_bands(const harris_launch::Params& p, dim3 grid, dim3 block, hipStream_t stream) {
+    if (p.flags & HARRIS_TUNE_CACHED_LOADS) hipLaunchKernelGGL((harris_fused_kernel<In, PX, D, kAuxDefault>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((harris_fused_kernel<In, PX, D, kAuxNonTemporal>), grid, block, 0, stream, p);
+    return hipGetLastError();
+}
+
+template <typename In, int PX, int RW>
+hipError_t launch_tiles(const harris_launch::Params& p, dim3 grid, dim3 block, hipStream_t stream) {
+    const size_t lds = (size_t)(block.x / kWave) * 4 * kWave * PX * sizeof(float);
+    if (p.flags & HARRIS_TUNE_CACHED_LOADS) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault>), grid, block, lds, stream, p);
+    else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal>), grid, block, lds, stream, p);
     return hipGetLastError();
 }
 
 template <typename In, int PX>
-hipError_t launch_px(const harris_launch::Params& p, int prefetch, dim3 grid, dim3 block, hipStream_t stream) {
-    switch (prefetch) {
-        case 1: return launch_one<In, PX, 1>(p, grid, block, stream);
-        case 2: return launch_one<In, PX, 2>(p, grid, block, stream);
-        case 3: return launch_one<In, PX, 3>(p, grid, block, stream);
-        case 6: return launch_one<In, PX, 6>(p, grid, block, stream);
+hipError_t launch_px(const harris_launch::Params& p, const harris_tuning& t, dim3 grid, dim3 block, hipStream_t stream) {
+    if (t.schedule == HARRIS_SCHEDULE_TILES) {
+        if constexpr (PX <= 4) {
+            switch (t.rows) {
+                case 4: return launch_tiles<In, PX, 4>(p, grid, block, stream);
+                case 8: return launch_tiles<In, PX, 8>(p, grid, block, stream);
+                default: return hipErrorInvalidValue;
+            }
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
+    switch (t.prefetch) {
+        case 1: return launch_bands<In, PX, 1>(p, grid, block, stream);
+        case 2: return launch_bands<In, PX, 2>(p, grid, block, stream);
+        case 3: return launch_bands<In, PX, 3>(p, grid, block, stream);
+        case 6: return launch_bands<In, PX, 6>(p, grid, block, stream);
         default: return hipErrorInvalidValue;
     }
 }
 
 template <typename In>
-hipError_t launch_in(const harris_launch::Params& p, int px, int prefetch, dim3 grid, dim3 block, hipStream_t stream) {
-    switch (px) {
-        case 1: return launch_px<In, 1>(p, prefetch, grid, block, stream);
-        case 2: return launch_px<In, 2>(p, prefetch, grid, block, stream);
-        case 4: return launch_px<In, 4>(p, prefetch, grid, block, stream);
-        case 8: return launch_px<In, 8>(p, prefetch, grid, block, stream);
+hipError_t launch_in(const harris_launch::Params& p, const harris_tuning& t, dim3 grid, dim3 block, hipStream_t stream) {
+    switch (t.px) {
+        case 1: return launch_px<In, 1>(p, t, grid, block, stream);
+        case 2: return launch_px<In, 2>(p, t, grid, block, stream);
+        case 4: return launch_px<In, 4>(p, t, grid, block, stream);
+        case 8: return launch_px<In, 8>(p, t, grid, block, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -359,8 +470,8 @@ namespace harris_launch {
 int launch(const Params& p, const harris_tuning& shape, long long n_blocks, int dtype, void* stream) {
     const dim3 grid((unsigned)n_blocks), block((unsigned)(shape.waves_per_block * kWave));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = dtype == HARRIS_U8 ? launch_in<uint8_t>(p, shape.px, shape.prefetch, grid, block, s)
-                                      : launch_in<float>(p, shape.px, shape.prefetch, grid, block, s);
+    hipError_t e = dtype == HARRIS_U8 ? launch_in<uint8_t>(p, shape, grid, block, s)
+                                      : launch_in<float>(p, shape, grid, block, s);
     return e == hipSuccess ? HARRIS_OK : HARRIS_ERR_LAUNCH;
 }
 

@@ -16,10 +16,10 @@ struct Params {
     float* out;             // device, [batch][n][m]
     int H, W;               // input rows, columns
     int n, m;               // result rows, columns (H-4, W-4)
-    int rows_per_band;      // result rows per band
+    int rows_per_band;      // result rows per band (BANDS) or per tile (TILES)
     unsigned n_strips;      // strips per band
     unsigned tiles_per_image;  // n_bands * n_strips
-    unsigned n_tiles;       // batch * tiles_per_image: one wavefront each
+    unsigned n_tiles;       // batch * tiles_per_image: one wavefront (BANDS) or workgroup (TILES) each
     float wr, wg, wb;       // gray weights, times the Sobel scale (and 1/255 for 8-bit input)
     float k;                // coarsity constant
     float wc;               // centre weight of the [1 wc 1] window taps

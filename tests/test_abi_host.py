@@ -40,7 +40,7 @@ def test_version_and_strerror(pkg):
 
 def test_plan_picks_widest_vector_path(pkg):
     shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
-    assert shape["px"] == 4 and blocks > 256 and shape["rows_per_band"] >= 8
+    assert shape["px"] == 4 and blocks > 256 and shape["rows"] >= 8
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 98)[0]["px"] == 2          # W even, not a multiple of 4
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 97)[0]["px"] == 1          # odd W
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 96, rgb_align=4)[0]["px"] == 1   # misaligned input
@@ -52,15 +52,34 @@ def test_plan_picks_widest_vector_path(pkg):
 def test_plan_tile_arithmetic(pkg):
     # 252 result columns per wavefront at px = 4; 2556 columns -> 11 strips; 1532 rows in
     # bands of 16 -> 96 bands; 4 wavefronts per workgroup.
-    t = dict(px=4, rows_per_band=16, prefetch=3, waves_per_block=4, flags=0)
+    t = dict(schedule=pkg.HARRIS_SCHEDULE_BANDS, px=4, rows=16, prefetch=3, waves_per_block=4, flags=pkg.HARRIS_TUNE_STREAM_LOADS)
     shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=t)
     assert shape == t and blocks == (11 * 96 + 3) // 4
-    shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 3, 9, 9, tuning=dict(px=1, rows_per_band=2, prefetch=1, waves_per_block=1, flags=3))
+    shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 3, 9, 9, tuning=dict(schedule=1, px=1, rows=2, prefetch=1, waves_per_block=1, flags=3))
     assert blocks == 3 * 3 * 1
+    # tiles: 8 wavefronts x 8 rows give 60 result rows per tile -> 26 tiles down, 11 across,
+    # one workgroup each
+    t = dict(schedule=pkg.HARRIS_SCHEDULE_TILES, px=4, rows=8, prefetch=0, waves_per_block=8, flags=pkg.HARRIS_TUNE_CACHED_LOADS)
+    shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=t)
+    assert shape == t and blocks == 26 * 11
     # empty results plan to zero workgroups
     assert pkg.harris_plan(pkg.HARRIS_F32, 0, 64, 64)[1] == 0
     assert pkg.harris_plan(pkg.HARRIS_F32, 2, 4, 64)[1] == 0
     assert pkg.harris_plan(pkg.HARRIS_F32, 2, 64, 4)[1] == 0
+
+
+def test_plan_defaults_follow_the_problem_size(pkg):
+    small, _ = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
+    assert small["schedule"] == pkg.HARRIS_SCHEDULE_BANDS and small["waves_per_block"] == 1
+    assert small["flags"] & pkg.HARRIS_TUNE_STREAM_LOADS and not small["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS
+    # 11 strips x 67 bands of 23 rows = 737 wavefronts: at most 3 per CU, 27 row steps each
+    assert small["rows"] == 23
+    big, blocks = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920)
+    assert big["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS and big["waves_per_block"] == 4 and big["rows"] == 32
+    assert blocks == 64 * 34 * 8 // 4
+    # an explicit policy is kept
+    kept, _ = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920, tuning=dict(flags=pkg.HARRIS_TUNE_STREAM_LOADS))
+    assert kept["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS
 
 
 def test_plan_rejects_bad_arguments(pkg):
@@ -73,7 +92,9 @@ def test_plan_rejects_bad_arguments(pkg):
         with pytest.raises(E) as e:
             pkg.harris_plan(*args)
         assert e.value.status == status
-    for bad in (dict(px=3), dict(px=4, prefetch=5), dict(px=4, waves_per_block=3), dict(flags=8), dict(rows_per_band=-1)):
+    for bad in (dict(px=3), dict(px=4, prefetch=5), dict(px=4, waves_per_block=3), dict(flags=16), dict(flags=12), dict(rows=-1),
+                dict(schedule=3), dict(schedule=2, rows=5), dict(schedule=2, waves_per_block=1), dict(schedule=2, waves_per_block=17),
+                dict(schedule=2, prefetch=3), dict(schedule=2, px=8)):
         with pytest.raises(E) as e:
             pkg.harris_plan(0, 1, 64, 64, tuning=bad)
         assert e.value.status == -3

@@ -116,10 +116,29 @@ def test_f32_every_kernel_instance(gpu, oracle, px, prefetch):
     H, W = 45, 8 * 67            # 536 columns: 2-3 strips at px 4/8, 5 at px 2, 9 at px 1
     rgb = hi.white_noise_f32(7, 2, H, W)
     want = oracle.harris(rgb, K)
-    for rows, wpb, flags in ((7, 4, 0), (10, 1, 1), (64, 2, 2), (1, 4, 3)):
-        tune = dict(px=px, rows_per_band=rows, prefetch=prefetch, waves_per_block=wpb, flags=flags)
+    for rows, wpb, flags in ((7, 4, 0), (10, 1, 1 | 4), (64, 2, 2 | 8), (1, 4, 3)):
+        tune = dict(schedule=1, px=px, rows=rows, prefetch=prefetch, waves_per_block=wpb, flags=flags)
         say("case f32 2x3x%dx%d %s" % (H, W, tune))
         check(run_gpu(gpu, rgb, k=K, tuning=tune), want)
+
+
+@pytest.mark.parametrize("px", [1, 2, 4])
+@pytest.mark.parametrize("rows", [4, 8])
+def test_tile_schedule_every_kernel_instance(gpu, oracle, px, rows):
+    H, W = 75, 8 * 67
+    for rgb in (hi.white_noise_f32(17, 2, H, W), hi.white_noise_u8(18, 2, H, W)):
+        want = oracle.harris(rgb, K)
+        for waves, flags in ((2, 0), (3, 2 | 4), (8, 8), (16, 0)):
+            tune = dict(schedule=2, px=px, rows=rows, waves_per_block=waves, flags=flags)
+            say("case tiles %s 2x3x%dx%d %s" % (rgb.dtype, H, W, tune))
+            check(run_gpu(gpu, rgb, k=K, tuning=tune), want)
+
+
+def test_tile_schedule_shapes(gpu, oracle):
+    for H, W in SHAPES:
+        rgb = hi.white_noise_f32(200 + H + W, 2, H, W)
+        say("case tiles f32 2x3x%dx%d" % (H, W))
+        check(run_gpu(gpu, rgb, k=K, tuning=dict(schedule=2)), oracle.harris(rgb, K))
 
 
 @pytest.mark.parametrize("px", [1, 2, 4, 8])
@@ -129,7 +148,7 @@ def test_u8_every_kernel_instance(gpu, oracle, px, prefetch):
     rgb = hi.white_noise_u8(8, 2, H, W)
     want = oracle.harris(rgb, K)
     for rows, wpb, flags in ((5, 4, 0), (13, 1, 3)):
-        tune = dict(px=px, rows_per_band=rows, prefetch=prefetch, waves_per_block=wpb, flags=flags)
+        tune = dict(schedule=1, px=px, rows=rows, prefetch=prefetch, waves_per_block=wpb, flags=flags)
         say("case u8 2x3x%dx%d %s" % (H, W, tune))
         check(run_gpu(gpu, rgb, k=K, tuning=tune), want)
 
