@@ -25,6 +25,21 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
+
+# HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
+# for the kernel sources they were taken with: (sha256 of the csrc files, {workload: bytes}).
+TRAFFIC_SOURCES_SHA256 = "ba05b4741204c3eee9a9c82e72097955eaa6b4eb257b739934557f6a24a2e9e3"
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 66681012, "rects_f32_64x1080x1920": 2204427539}
+
+
+def kernel_sources_sha256():
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2212_12035_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()
 WORKLOAD = "noise_f32_1536x2560"
 K_COARSITY = 0.04
 
@@ -82,6 +97,7 @@ def main():
     ins = [base] + [torch.roll(base, shifts=i, dims=2) for i in range(1, n_pairs)]
     outs = [torch.empty((B, n, m), dtype=torch.float32, device=dev) for _ in range(n_pairs)]
 
+    explicit_tuning = any((args.schedule, args.px, args.rows, args.prefetch, args.waves_per_block, args.flags))
     tuning = pkg.HarrisTuning(args.schedule, args.px, args.rows, args.prefetch, args.waves_per_block, args.flags)
     shape, n_blocks = pkg.harris_plan(pkg.HARRIS_U8 if is_u8 else pkg.HARRIS_F32, B, H, W, tuning=tuning)
     stream = torch.cuda.current_stream(dev)
@@ -162,7 +178,8 @@ def main():
                    "buffer_pairs": n_pairs, "cache": "warm" if args.warm_cache else "cold (rotating buffers)",
                    "launch": shape, "workgroups": n_blocks},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": TRAFFIC_BYTES.get(args.workload) if kernel_sources_sha256() == TRAFFIC_SOURCES_SHA256 and not explicit_tuning else None,
                      "algorithmic_bytes_per_launch": algo_bytes,
                      "launch_us_avg_over_timed_region": round(launch_us, 3),
                      "launch_us_single_median": round(single_med_us, 3)},

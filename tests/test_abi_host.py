@@ -72,8 +72,8 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     small, _ = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
     assert small["schedule"] == pkg.HARRIS_SCHEDULE_BANDS and small["waves_per_block"] == 1
     assert small["flags"] & pkg.HARRIS_TUNE_STREAM_LOADS and not small["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS
-    # 11 strips x 67 bands of 23 rows = 737 wavefronts: at most 3 per CU, 27 row steps each
-    assert small["rows"] == 23
+    # 11 strips x 91 bands of 17 rows = 1001 wavefronts: one per SIMD
+    assert small["rows"] == 17
     big, blocks = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920)
     assert big["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS and big["waves_per_block"] == 4 and big["rows"] == 32
     assert blocks == 64 * 34 * 8 // 4
