@@ -73,10 +73,11 @@ typedef enum harris_window {
  *             from the size.
  *   px        pixels per lane along x: 1, 2, 4 or (BANDS only) 8; must divide W and match
  *             the pointer alignment, else HARRIS_ERR_ARG; 0 = widest of 1, 2, 4 that fits.
- *   rows      BANDS: result rows per band (>= 1).  TILES: input rows per wavefront, 4 or
- *             8.  0 = chosen from the size.
- *   prefetch  BANDS only: input rows kept in flight per wavefront, 1, 2, 3 or 6; 0 = default.
- *   waves_per_block  BANDS: 1, 2 or 4.  TILES: 2 to 16.  0 = default.
+ *   rows      BANDS: result rows per band (>= 1).  TILES: input rows per wavefront: 4 or 8,
+ *             and with px = 4 also 5, 6, 9 or 10.  0 = chosen from the size.
+ *   prefetch  BANDS only: input rows kept in flight per wavefront, 2, 3 or 6; 0 = default.
+ *   waves_per_block  BANDS: 1, 2 or 4 (2: two bands of a strip that start on shared rows;
+ *             4: the same for two adjacent strips).  TILES: 2 to 16.  0 = default.
  *   flags     HARRIS_TUNE_* bits.
  */
 typedef struct harris_tuning {

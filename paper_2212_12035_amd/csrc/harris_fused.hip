@@ -175,8 +175,8 @@ struct LineBuffers {
 // One row step.  GS is the ring slot that receives this step's gray row.
 // STAGE 0: gray only (first two rows of a band); 1: also Sobel and products (next
 // two rows); 2: also window sums, coarsity and the store of one result row.
-template <int STAGE, int GS, int PX>
-__device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[PX], float wc, float k,
+template <int STAGE, int GS, int PX, bool BINOM>
+__device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[PX], float k,
                                          __amdgpu_buffer_rsrc_t out_rs, uint32_t store_voff) {
     constexpr int PS = (GS + 1) % 3;          // product slot written at this step
 #pragma unroll
@@ -204,18 +204,37 @@ __device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[
         }
     }
     if constexpr (STAGE >= 2) {
-        // Stage a4, separated: [1 wc 1] down the column, then along the row (wc = 1 for
-        // the unweighted sum, 2 for the binomial window).
+        // Stage a4, separated: [1 c 1] down the column, then along the row (c = 1 for the
+        // unweighted sum, 2 for the binomial window).  Along the row neighbouring results
+        // share a pair sum, and every value that comes from the lane to the right is an
+        // operand of an addition, so that its lane shift rides on that addition.
         float s[3][PX];
 #pragma unroll
         for (int q = 0; q < 3; ++q) {
             float v[PX + 2];
 #pragma unroll
-            for (int i = 0; i < PX; ++i)
-                v[i] = fmaf(wc, lb.p[(PS + 2) % 3][q][i], lb.p[(PS + 1) % 3][q][i] + lb.p[PS][q][i]);
+            for (int i = 0; i < PX; ++i) {
+                const float ends = lb.p[(PS + 1) % 3][q][i] + lb.p[PS][q][i];
+                const float mid = lb.p[(PS + 2) % 3][q][i];
+                v[i] = BINOM ? fmaf(2.0f, mid, ends) : ends + mid;
+            }
             fetch_halo<PX>(v);
+            if constexpr (BINOM) {
+                float pair[PX + 1];                       // v[i] + v[i+1]
 #pragma unroll
-            for (int i = 0; i < PX; ++i) s[q][i] = fmaf(wc, v[i + 1], v[i] + v[i + 2]);
+                for (int i = 0; i <= PX; ++i) pair[i] = v[i + 1] + v[i];
+#pragma unroll
+                for (int i = 0; i < PX; ++i) s[q][i] = pair[i] + pair[i + 1];   // v[i] + 2 v[i+1] + v[i+2]
+            } else if constexpr (PX == 1) {
+                s[q][0] = (v[1] + v[0]) + v[2];
+            } else {
+#pragma unroll
+                for (int j = 0; j < PX / 2; ++j) {
+                    const float pair = v[2 * j + 2] + v[2 * j + 1];
+                    s[q][2 * j] = v[2 * j] + pair;
+                    s[q][2 * j + 1] = v[2 * j + 3] + pair;
+                }
+            }
         }
         // Stage a5.
         float o[PX];
@@ -239,10 +258,8 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned nb) {
     return x < r ? x * (q + 1) + j : r * (q + 1) + (x - r) * q + j;
 }
 
-template <typename In, int PX, int D, int LAUX>
+template <typename In, int PX, int D, int LAUX, bool BINOM>
 __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::Params p) {
-    constexpr int VL = harris_launch::valid_lanes(PX);
-    constexpr int PITCH = VL * PX;
     constexpr int U = lcm_c(3, D);            // row steps per loop trip: ring slots stay static
 
     const unsigned lane = threadIdx.x % kWave;
@@ -250,25 +267,32 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
     const unsigned waves_per_block = blockDim.x / kWave;
     unsigned blk = blockIdx.x;
     if (!(p.flags & HARRIS_TUNE_NO_XCD_REMAP)) blk = xcd_contiguous(blk, gridDim.x);
-    const unsigned tile = blk * waves_per_block + wave;
-    if (tile >= p.n_tiles) return;            // uniform per wavefront; no barrier is ever used
 
-    const unsigned img = tile / p.tiles_per_image;
-    const unsigned rem = tile % p.tiles_per_image;
-    const int band = (int)(rem / p.n_strips);
-    const int strip = (int)(rem % p.n_strips);
+    // A workgroup of 2 or 4 wavefronts holds two vertically adjacent bands (of one strip,
+    // or of two adjacent strips): band 2j walks upwards and band 2j+1 downwards, so both
+    // begin on the four input rows they share, and the second request for those rows (and
+    // for the cache line two adjacent strips share) is served by the CU's vector cache.
+    const unsigned group_h = waves_per_block >= 2 ? 2u : 1u;
+    const unsigned group_w = waves_per_block / group_h;
+    const unsigned img = blk / p.blocks_per_image;
+    const unsigned rem = blk % p.blocks_per_image;
+    const int band = (int)((rem / p.blocks_x) * group_h + wave / group_w);
+    const int strip = (int)((rem % p.blocks_x) * group_w + wave % group_w);
+    if (band >= (int)p.n_bands || strip >= (int)p.n_strips) return;   // uniform per wavefront; no barrier is ever used
 
     const int y0 = band * p.rows_per_band;                      // first result row of the band
     const int rows = min(p.rows_per_band, p.n - y0);            // result rows of this band (>= 1)
     const int steps = rows + 4;                                 // input rows consumed
-    const bool up = !(p.flags & HARRIS_TUNE_NO_ALTERNATE) && (band & 1);
+    const bool up = !(p.flags & HARRIS_TUNE_NO_ALTERNATE) && !(band & 1);
 
-    const unsigned col = (unsigned)(strip * PITCH) + lane * PX; // first column of this lane (input and result)
+    // A strip yields p.strip_pitch result columns (at most 64*PX - 4, the same for every
+    // strip so that all wavefronts carry the same load); the lanes beyond only supply halo.
+    const unsigned col = (unsigned)strip * p.strip_pitch + lane * PX; // first column of this lane (input and result)
     const unsigned lcol = min(col, (unsigned)(p.W - PX));       // loads stay inside the row
     const uint32_t load_voff = lcol * (uint32_t)sizeof(In);
-    // Lanes that only supply halo store nothing: an offset beyond any row.  Lanes whose
-    // columns lie right of the result row are dropped by the buffer's range check.
-    const uint32_t store_voff = lane < (unsigned)VL ? col * 4u : 0x80000000u;
+    // Halo-only lanes store nothing: an offset beyond any row.  Lanes whose columns lie
+    // right of the result row are dropped by the buffer's range check.
+    const uint32_t store_voff = lane * PX < p.strip_pitch ? col * 4u : 0x80000000u;
     const uint32_t in_row_bytes = (uint32_t)p.W * (uint32_t)sizeof(In);
     const uint32_t out_row_bytes = (uint32_t)p.m * 4u;
 
@@ -304,7 +328,7 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
         __builtin_amdgcn_sched_barrier(0);
         load_row<In, PX, LAUX>(queue[t % D], in_row_ptr(t + D), plane, in_row_size(t + D), load_voff);
         __builtin_amdgcn_sched_barrier(0);
-        row_step<(t < 2 ? 0 : 1), t % 3, PX>(lb, gc, p.wc, p.k, no_store, store_voff);
+        row_step<(t < 2 ? 0 : 1), t % 3, PX, BINOM>(lb, gc, p.k, no_store, store_voff);
     });
 
     for (int t0 = 4; t0 < steps; t0 += U) {
@@ -321,7 +345,7 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
             // past the band's end get an empty descriptor and store nothing.
             const int orow = max(0, min(p.n - 1, up ? y0 + rows + 3 - t : y0 + t - 4));
             const __amdgpu_buffer_rsrc_t out_rs = make_rsrc(img_out + (size_t)orow * p.m, t < steps ? out_row_bytes : 0u);
-            row_step<2, (4 + u) % 3, PX>(lb, gc, p.wc, p.k, out_rs, store_voff);
+            row_step<2, (4 + u) % 3, PX, BINOM>(lb, gc, p.k, out_rs, store_voff);
         });
     }
 }
@@ -339,10 +363,8 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
 // its RW+4 gray rows and stores RW result rows (the last wavefront has no neighbour
 // below and stores RW-4).  A tile yields NW*RW-4 result rows; the tile below re-reads
 // four rows.
-template <typename In, int PX, int RW, int LAUX>
+template <typename In, int PX, int RW, int LAUX, bool BINOM>
 __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::Params p) {
-    constexpr int VL = harris_launch::valid_lanes(PX);
-    constexpr int PITCH = VL * PX;
     extern __shared__ __align__(16) float halo_lds[];           // [NW][4][64][PX]
 
     const unsigned lane = threadIdx.x % kWave;
@@ -362,10 +384,10 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
     const int y_end = min(p.n, (band + 1) * tile_rows);         // result rows of this tile end here
     const int out_rows = max(0, min(RW, y_end - y_wave));       // result rows this wavefront stores
 
-    const unsigned col = (unsigned)(strip * PITCH) + lane * PX;
+    const unsigned col = (unsigned)strip * p.strip_pitch + lane * PX;
     const unsigned lcol = min(col, (unsigned)(p.W - PX));
     const uint32_t load_voff = lcol * (uint32_t)sizeof(In);
-    const uint32_t store_voff = lane < (unsigned)VL ? col * 4u : 0x80000000u;
+    const uint32_t store_voff = lane * PX < p.strip_pitch ? col * 4u : 0x80000000u;
     const uint32_t in_row_bytes = (uint32_t)p.W * (uint32_t)sizeof(In);
     const uint32_t out_row_bytes = (uint32_t)p.m * 4u;
 
@@ -398,8 +420,8 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 #pragma unroll
             for (int i = 0; i < PX; ++i) my_halo[(size_t)t * kWave * PX + i] = gc[i];
         }
-        if constexpr (t < 4) row_step<(t < 2 ? 0 : 1), t % 3, PX>(lb, gc, p.wc, p.k, no_store, store_voff);
-        else row_step<2, t % 3, PX>(lb, gc, p.wc, p.k, out_desc(t), store_voff);
+        if constexpr (t < 4) row_step<(t < 2 ? 0 : 1), t % 3, PX, BINOM>(lb, gc, p.k, no_store, store_voff);
+        else row_step<2, t % 3, PX, BINOM>(lb, gc, p.k, out_desc(t), store_voff);
     });
 
     __syncthreads();
@@ -410,23 +432,35 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
             constexpr int t = decltype(tt)::value;
 #pragma unroll
             for (int i = 0; i < PX; ++i) gc[i] = below[(size_t)(t - RW) * kWave * PX + i];
-            row_step<2, t % 3, PX>(lb, gc, p.wc, p.k, out_desc(t), store_voff);
+            row_step<2, t % 3, PX, BINOM>(lb, gc, p.k, out_desc(t), store_voff);
         });
     }
 }
 
 template <typename In, int PX, int D>
 hipError_t launch_bands(const harris_launch::Params& p, dim3 grid, dim3 block, hipStream_t stream) {
-    if (p.flags & HARRIS_TUNE_CACHED_LOADS) hipLaunchKernelGGL((harris_fused_kernel<In, PX, D, kAuxDefault>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((harris_fused_kernel<In, PX, D, kAuxNonTemporal>), grid, block, 0, stream, p);
+    const bool cached = p.flags & HARRIS_TUNE_CACHED_LOADS;
+    if (p.binomial) {
+        if (cached) hipLaunchKernelGGL((harris_fused_kernel<In, PX, D, kAuxDefault, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((harris_fused_kernel<In, PX, D, kAuxNonTemporal, true>), grid, block, 0, stream, p);
+    } else {
+        if (cached) hipLaunchKernelGGL((harris_fused_kernel<In, PX, D, kAuxDefault, false>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((harris_fused_kernel<In, PX, D, kAuxNonTemporal, false>), grid, block, 0, stream, p);
+    }
     return hipGetLastError();
 }
 
 template <typename In, int PX, int RW>
 hipError_t launch_tiles(const harris_launch::Params& p, dim3 grid, dim3 block, hipStream_t stream) {
     const size_t lds = (size_t)(block.x / kWave) * 4 * kWave * PX * sizeof(float);
-    if (p.flags & HARRIS_TUNE_CACHED_LOADS) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault>), grid, block, lds, stream, p);
-    else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal>), grid, block, lds, stream, p);
+    const bool cached = p.flags & HARRIS_TUNE_CACHED_LOADS;
+    if (p.binomial) {
+        if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, true>), grid, block, lds, stream, p);
+        else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, true>), grid, block, lds, stream, p);
+    } else {
+        if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, false>), grid, block, lds, stream, p);
+        else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, false>), grid, block, lds, stream, p);
+    }
     return hipGetLastError();
 }
 
@@ -437,14 +471,23 @@ hipError_t launch_px(const harris_launch::Params& p, const harris_tuning& t, dim
             switch (t.rows) {
                 case 4: return launch_tiles<In, PX, 4>(p, grid, block, stream);
                 case 8: return launch_tiles<In, PX, 8>(p, grid, block, stream);
-                default: return hipErrorInvalidValue;
+                default: break;
             }
+            if constexpr (PX == 4) {
+                switch (t.rows) {
+                    case 5: return launch_tiles<In, PX, 5>(p, grid, block, stream);
+                    case 6: return launch_tiles<In, PX, 6>(p, grid, block, stream);
+                    case 9: return launch_tiles<In, PX, 9>(p, grid, block, stream);
+                    case 10: return launch_tiles<In, PX, 10>(p, grid, block, stream);
+                    default: break;
+                }
+            }
+            return hipErrorInvalidValue;
         } else {
             return hipErrorInvalidValue;
         }
     }
     switch (t.prefetch) {
-        case 1: return launch_bands<In, PX, 1>(p, grid, block, stream);
         case 2: return launch_bands<In, PX, 2>(p, grid, block, stream);
         case 3: return launch_bands<In, PX, 3>(p, grid, block, stream);
         case 6: return launch_bands<In, PX, 6>(p, grid, block, stream);

@@ -18,11 +18,14 @@ struct Params {
     int n, m;               // result rows, columns (H-4, W-4)
     int rows_per_band;      // result rows per band (BANDS) or per tile (TILES)
     unsigned n_strips;      // strips per band
-    unsigned tiles_per_image;  // n_bands * n_strips
-    unsigned n_tiles;       // batch * tiles_per_image: one wavefront (BANDS) or workgroup (TILES) each
+    unsigned strip_pitch;   // result columns per strip (a multiple of px, at most valid_lanes(px)*px)
+    unsigned n_bands;       // bands (BANDS) or tiles down the image (TILES)
+    unsigned tiles_per_image;  // n_bands * n_strips (TILES: one workgroup each)
+    unsigned blocks_x;      // BANDS: workgroups across a row of bands
+    unsigned blocks_per_image;  // BANDS: workgroups per image
     float wr, wg, wb;       // gray weights, times the Sobel scale (and 1/255 for 8-bit input)
     float k;                // coarsity constant
-    float wc;               // centre weight of the [1 wc 1] window taps
+    int binomial;           // 1: window [1 2 1; 2 4 2; 1 2 1], 0: unweighted 3x3 sum
     unsigned flags;         // HARRIS_TUNE_* bits
 };
 

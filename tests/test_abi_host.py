@@ -40,7 +40,7 @@ def test_version_and_strerror(pkg):
 
 def test_plan_picks_widest_vector_path(pkg):
     shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
-    assert shape["px"] == 4 and blocks > 256 and shape["rows"] >= 8
+    assert shape["px"] == 4 and blocks > 128 and shape["rows"] >= 4
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 98)[0]["px"] == 2          # W even, not a multiple of 4
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 97)[0]["px"] == 1          # odd W
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 96, rgb_align=4)[0]["px"] == 1   # misaligned input
@@ -54,8 +54,8 @@ def test_plan_tile_arithmetic(pkg):
     # bands of 16 -> 96 bands; 4 wavefronts per workgroup.
     t = dict(schedule=pkg.HARRIS_SCHEDULE_BANDS, px=4, rows=16, prefetch=3, waves_per_block=4, flags=pkg.HARRIS_TUNE_STREAM_LOADS)
     shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=t)
-    assert shape == t and blocks == (11 * 96 + 3) // 4
-    shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 3, 9, 9, tuning=dict(schedule=1, px=1, rows=2, prefetch=1, waves_per_block=1, flags=3))
+    assert shape == t and blocks == 6 * 48          # 2 strips x 2 bands per workgroup: ceil(11/2) x ceil(96/2)
+    shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 3, 9, 9, tuning=dict(schedule=1, px=1, rows=2, prefetch=2, waves_per_block=1, flags=3))
     assert blocks == 3 * 3 * 1
     # tiles: 8 wavefronts x 8 rows give 60 result rows per tile -> 26 tiles down, 11 across,
     # one workgroup each
@@ -69,14 +69,18 @@ def test_plan_tile_arithmetic(pkg):
 
 
 def test_plan_defaults_follow_the_problem_size(pkg):
-    small, _ = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
-    assert small["schedule"] == pkg.HARRIS_SCHEDULE_BANDS and small["waves_per_block"] == 1
+    small, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
+    # one tile per CU: 11 strips x 23 tiles of 9 wavefronts x 8 rows (68 result rows) = 253 workgroups
+    assert small["schedule"] == pkg.HARRIS_SCHEDULE_TILES and (small["rows"], small["waves_per_block"]) == (8, 9) and blocks == 253
     assert small["flags"] & pkg.HARRIS_TUNE_STREAM_LOADS and not small["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS
-    # 11 strips x 91 bands of 17 rows = 1001 wavefronts: one per SIMD
-    assert small["rows"] == 17
+    # too many strips for one tile per CU: bands, one wavefront per SIMD (17 strips x 59 bands of 48 rows)
+    mid, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4256)
+    assert mid["schedule"] == pkg.HARRIS_SCHEDULE_BANDS and mid["rows"] == 48 and mid["waves_per_block"] == 1 and blocks == 1003
+    # asking for bands keeps bands
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=dict(schedule=1))[0]["rows"] == 17
     big, blocks = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920)
     assert big["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS and big["waves_per_block"] == 4 and big["rows"] == 32
-    assert blocks == 64 * 34 * 8 // 4
+    assert blocks == 64 * 17 * 4
     # an explicit policy is kept
     kept, _ = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920, tuning=dict(flags=pkg.HARRIS_TUNE_STREAM_LOADS))
     assert kept["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS
@@ -93,7 +97,7 @@ def test_plan_rejects_bad_arguments(pkg):
             pkg.harris_plan(*args)
         assert e.value.status == status
     for bad in (dict(px=3), dict(px=4, prefetch=5), dict(px=4, waves_per_block=3), dict(flags=16), dict(flags=12), dict(rows=-1),
-                dict(schedule=3), dict(schedule=2, rows=5), dict(schedule=2, waves_per_block=1), dict(schedule=2, waves_per_block=17),
+                dict(schedule=3), dict(schedule=2, rows=7), dict(schedule=2, px=2, rows=5), dict(schedule=2, waves_per_block=1), dict(schedule=2, waves_per_block=17),
                 dict(schedule=2, prefetch=3), dict(schedule=2, px=8)):
         with pytest.raises(E) as e:
             pkg.harris_plan(0, 1, 64, 64, tuning=bad)
