@@ -51,20 +51,25 @@ int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const
     const long long n_strips = m > 0 ? (m + max_pitch - 1) / max_pitch : 0;
     const long long pitch = n_strips > 0 ? ((m + n_strips - 1) / n_strips + t.px - 1) / t.px * t.px : max_pitch;
 
-    // Bytes the launch moves; against the 256 MB last-level cache this decides the load policy
-    // and whether there is enough work for four-wavefront workgroups.
+    // Bytes the launch moves.  Measured rule for the load policy: float32 problems beyond about
+    // half the 256 MB last-level cache run faster with default-policy loads (the rows two tiles
+    // share and the line two strips share are then found in the caches), smaller ones and 8-bit
+    // input with non-temporal loads.
     const long long elem = elem_size(dtype);
     const long long footprint = (long long)batch * (3LL * H * W * elem + 4LL * n * m);
-    const bool large = footprint > (256LL << 20);
+    const bool cached = dtype == HARRIS_F32 && footprint > (128LL << 20);
     if (!(t.flags & (HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS)))
-        t.flags |= large ? HARRIS_TUNE_CACHED_LOADS : HARRIS_TUNE_STREAM_LOADS;
+        t.flags |= cached ? HARRIS_TUNE_CACHED_LOADS : HARRIS_TUNE_STREAM_LOADS;
 
-    // A problem that one pass over the 256 CUs can hold is fastest as one tile per CU: all
-    // CUs then carry the same load and finish together (measured on 1536x2560: 14.0 us
-    // against 14.6 us for the best band shape).  Find the smallest tile of NW wavefronts x RW
-    // rows that covers the image with at most 256 tiles; RW in order of measured preference.
-    int tile_rw = 0, tile_nw = 0;
-    if (!large && t.px == 4 && batch > 0 && n_strips > 0 && (long long)batch * n_strips <= 256) {
+    // Default tile shape.  A problem that one pass over the 256 CUs can hold is fastest as one
+    // tile per CU: all CUs then carry the same load and finish together (measured on
+    // 1536x2560: 14.0 us against 14.4 us for small tiles and 14.6 us for the best band shape).
+    // Find the smallest tile of NW wavefronts x RW rows that covers the problem with at most 256
+    // tiles; RW in order of measured preference.  Larger problems take many small tiles of
+    // 4 wavefronts x 4 rows, which keep the memory system busiest (measured on 2832x4256,
+    // 64x1080x1920 and 8192x8192 uint8).
+    int tile_rw = 4, tile_nw = 4;
+    if (footprint <= (128LL << 20) && t.px == 4 && batch > 0 && n_strips > 0 && (long long)batch * n_strips <= 256) {
         const long long max_bands = 256 / ((long long)batch * n_strips);
         const long long need_rows = (n + max_bands - 1) / max_bands + 4;     // input rows per tile
         static const int kRowsPerWave[] = {8, 9, 10, 6, 5, 4};
@@ -76,20 +81,21 @@ int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const
             if (best < 0 || nw * rw < best) { best = nw * rw; tile_rw = rw; tile_nw = (int)nw; }
         }
     }
-    if (t.schedule == 0) t.schedule = tile_rw != 0 && t.rows == 0 && t.waves_per_block == 0 && t.prefetch == 0
-                                          ? HARRIS_SCHEDULE_TILES : HARRIS_SCHEDULE_BANDS;
+    // px = 8 and a prefetch depth exist only in the band schedule.
+    if (t.schedule == 0) t.schedule = t.px <= 4 && t.prefetch == 0 ? HARRIS_SCHEDULE_TILES : HARRIS_SCHEDULE_BANDS;
 
     long long tile_rows;       // result rows per band or tile
     if (t.schedule == HARRIS_SCHEDULE_TILES) {
-        if (t.rows == 0 && t.waves_per_block == 0 && tile_rw != 0) { t.rows = tile_rw; t.waves_per_block = tile_nw; }
-        if (t.rows == 0) t.rows = 8;
-        if (t.waves_per_block == 0) t.waves_per_block = 8;
+        if (t.rows == 0 && t.waves_per_block == 0) { t.rows = tile_rw; t.waves_per_block = tile_nw; }
+        if (t.rows == 0) t.rows = 4;
+        if (t.waves_per_block == 0) t.waves_per_block = 4;
         const bool rows_ok = t.rows == 4 || t.rows == 8 || (t.px == 4 && (t.rows == 5 || t.rows == 6 || t.rows == 9 || t.rows == 10));
         if (!rows_ok || t.waves_per_block < 2 || t.waves_per_block > 16) return HARRIS_ERR_ARG;
         if (t.prefetch != 0) return HARRIS_ERR_ARG;
         if (t.px > 4) return HARRIS_ERR_ARG;                           // 8 rows of 8 pixels per lane do not fit the registers
         tile_rows = (long long)t.rows * t.waves_per_block - 4;
     } else {
+        const bool large = footprint > (256LL << 20);
         if (t.prefetch == 0) t.prefetch = large ? 6 : 3;
         if (!(t.prefetch == 2 || t.prefetch == 3 || t.prefetch == 6)) return HARRIS_ERR_ARG;
         if (t.waves_per_block == 0) t.waves_per_block = large ? 4 : 1;

@@ -73,17 +73,22 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     # one tile per CU: 11 strips x 23 tiles of 9 wavefronts x 8 rows (68 result rows) = 253 workgroups
     assert small["schedule"] == pkg.HARRIS_SCHEDULE_TILES and (small["rows"], small["waves_per_block"]) == (8, 9) and blocks == 253
     assert small["flags"] & pkg.HARRIS_TUNE_STREAM_LOADS and not small["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS
-    # too many strips for one tile per CU: bands, one wavefront per SIMD (17 strips x 59 bands of 48 rows)
+    # beyond one tile per CU: many tiles of 4 wavefronts x 4 rows (12 result rows); cached loads for large float32
     mid, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4256)
-    assert mid["schedule"] == pkg.HARRIS_SCHEDULE_BANDS and mid["rows"] == 48 and mid["waves_per_block"] == 1 and blocks == 1003
-    # asking for bands keeps bands
-    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=dict(schedule=1))[0]["rows"] == 17
+    assert (mid["schedule"], mid["rows"], mid["waves_per_block"]) == (2, 4, 4) and blocks == 17 * 236
+    assert mid["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS
     big, blocks = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920)
-    assert big["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS and big["waves_per_block"] == 4 and big["rows"] == 32
-    assert blocks == 64 * 17 * 4
+    assert (big["rows"], big["waves_per_block"]) == (4, 4) and big["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS and blocks == 64 * 90 * 8
+    u8, _ = pkg.harris_plan(pkg.HARRIS_U8, 1, 8192, 8192)
+    assert u8["flags"] & pkg.HARRIS_TUNE_STREAM_LOADS
     # an explicit policy is kept
     kept, _ = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920, tuning=dict(flags=pkg.HARRIS_TUNE_STREAM_LOADS))
     assert kept["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS
+    # asking for bands gives bands: one wavefront per SIMD for small problems, four-wavefront groups for large
+    bands, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=dict(schedule=1))
+    assert (bands["rows"], bands["prefetch"], bands["waves_per_block"]) == (17, 3, 1) and blocks == 1001
+    bands, blocks = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920, tuning=dict(schedule=1))
+    assert (bands["rows"], bands["prefetch"], bands["waves_per_block"]) == (32, 6, 4) and blocks == 64 * 17 * 4
 
 
 def test_plan_rejects_bad_arguments(pkg):
@@ -96,7 +101,7 @@ def test_plan_rejects_bad_arguments(pkg):
         with pytest.raises(E) as e:
             pkg.harris_plan(*args)
         assert e.value.status == status
-    for bad in (dict(px=3), dict(px=4, prefetch=5), dict(px=4, waves_per_block=3), dict(flags=16), dict(flags=12), dict(rows=-1),
+    for bad in (dict(px=3), dict(px=4, prefetch=5), dict(schedule=1, px=4, waves_per_block=3), dict(waves_per_block=1), dict(flags=16), dict(flags=12), dict(rows=-1),
                 dict(schedule=3), dict(schedule=2, rows=7), dict(schedule=2, px=2, rows=5), dict(schedule=2, waves_per_block=1), dict(schedule=2, waves_per_block=17),
                 dict(schedule=2, prefetch=3), dict(schedule=2, px=8)):
         with pytest.raises(E) as e:
