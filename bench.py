@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "ba05b4741204c3eee9a9c82e72097955eaa6b4eb257b739934557f6a24a2e9e3"
-TRAFFIC_BYTES = {"noise_f32_1536x2560": 66681012, "rects_f32_64x1080x1920": 2204427539}
+TRAFFIC_SOURCES_SHA256 = "68929786fb1fc76b577ef10449ba5233c28c6fd1579c6d464fb538d5ba127fd5"
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 65648494, "rects_f32_64x1080x1920": 2196756563}
 
 
 def kernel_sources_sha256():
