@@ -58,6 +58,7 @@ def parse():
     ap.add_argument("--waves-per-block", type=int, default=0)
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-groupings", action="store_true", help="skip timing the unfused kernel groupings")
     ap.add_argument("--warm-cache", action="store_true", help="reuse one buffer pair (cache-resident; not the roofline number)")
     return ap.parse_args()
 
@@ -141,6 +142,35 @@ def main():
     singles = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)
     single_med_us = singles[len(singles) // 2]
 
+    # The thesis's kernel groupings (unfused baselines) on the same rotating buffers, for comparison.
+    groupings = None
+    if not args.no_groupings:
+        groupings = {}
+        ws_bytes = pkg.harris_grouped_workspace_bytes(1, B, H, W)
+        ws = torch.empty(max(1, ws_bytes // 4), dtype=torch.float32, device=dev)
+        reps = max(10, min(100, args.steps // 8))
+        for g in (1, 2, 3):
+            def gstep(i, g=g):
+                a, o = calls[i % n_pairs]
+                rc = lib.harris_coarsity_grouped(a, dtype_code, B, H, W, K_COARSITY, 1.0, 0, g, ctypes.c_void_p(ws.data_ptr()),
+                                                 ws_bytes, o, sptr)
+                if rc != 0:
+                    raise RuntimeError(pkg.harris_strerror(rc))
+            for i in range(3):
+                gstep(i)
+            torch.cuda.synchronize(dev)
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g0.record(stream)
+            for i in range(reps):
+                gstep(i)
+            g1.record(stream)
+            torch.cuda.synchronize(dev)
+            groupings["grouping_%d_us" % g] = round(g0.elapsed_time(g1) * 1e3 / reps, 2)
+        groupings["grouping_4_fused_us"] = round(launch_us, 2)
+        del ws
+        step(0)                                   # pair 0 holds the fused kernel's result again
+        torch.cuda.synchronize(dev)
+
     # Correctness of what was timed: pair 0 against the oracle (also the CPU baseline).
     got = outs[0].cpu().numpy()
     cpu = None
@@ -184,6 +214,7 @@ def main():
                      "launch_us_avg_over_timed_region": round(launch_us, 3),
                      "launch_us_single_median": round(single_med_us, 3)},
         "cpu_baseline": cpu,
+        "kernel_groupings": groupings,
         "max_abs_err_vs_oracle": max_err, "err_bound": bound,
     }
     print(json.dumps(result))

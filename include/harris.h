@@ -138,6 +138,28 @@ int harris_coarsity_ex(const void* rgb, int dtype, int batch, int H, int W, floa
 int harris_plan(int dtype, int batch, int H, int W, int rgb_align, int out_align,
                 const harris_tuning* tuning, harris_tuning* chosen, long long* n_blocks);
 
+/*
+ * The same result computed by several kernels that keep their intermediate images in
+ * device memory: the kernel groupings of the thesis's section 3.5.3 (table "Four
+ * different kernel groupings"), each preceded by a grayscale kernel.
+ *   grouping 1  [Sx] [Sy] [x] [+] [coarsity], one kernel per operator and image (10 launches)
+ *   grouping 2  [Sx, Sy, x] [+, coarsity]
+ *   grouping 3  [Sx, Sy] [x, +, coarsity]
+ *   grouping 4  one fused kernel: identical to harris_coarsity_ex without tuning
+ * These are untuned baselines for measuring what fusion buys, and a second
+ * implementation to cross-check the fused kernels; arguments as harris_coarsity_ex, plus
+ *   workspace        device memory for the intermediates, 4-byte aligned, owned by the
+ *                    caller, contents undefined afterwards; may be NULL for grouping 4
+ *   workspace_bytes  its size; at least harris_grouped_workspace_bytes(...) or
+ *                    HARRIS_ERR_ARG.  batch must not exceed 65535 for groupings 1-3.
+ */
+int harris_coarsity_grouped(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale,
+                            int window, int grouping, void* workspace, long long workspace_bytes,
+                            float* out, void* stream);
+
+/* Workspace bytes harris_coarsity_grouped needs; 0 for grouping 4; -1 for invalid arguments. Host only. */
+long long harris_grouped_workspace_bytes(int grouping, int batch, int H, int W);
+
 /* Static, NUL-terminated description of a harris_status value. */
 const char* harris_strerror(int status);
 

@@ -10,4 +10,5 @@ from .binding import (  # noqa: F401
     HARRIS_TUNE_CACHED_LOADS, HARRIS_TUNE_STREAM_LOADS,
     HarrisError, HarrisTuning, library_path, load_library,
     harris_coarsity, harris_coarsity_u8, harris_coarsity_ex, harris_plan, harris_strerror, harris_version,
+    harris_coarsity_grouped, harris_grouped_workspace_bytes,
 )

@@ -20,7 +20,7 @@ _LIB_PATH = os.path.join(_HERE, "libharris.so")
 
 #: every symbol include/harris.h declares
 EXPORTS = ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan",
-           "harris_strerror", "harris_version")
+           "harris_coarsity_grouped", "harris_grouped_workspace_bytes", "harris_strerror", "harris_version")
 
 
 class HarrisError(RuntimeError):
@@ -64,7 +64,11 @@ def load_library() -> ctypes.CDLL:
     lib.harris_coarsity_u8.argtypes = [vp, ci, ci, ci, cf, vp, vp]
     lib.harris_coarsity_ex.argtypes = [vp, ci, ci, ci, ci, cf, cf, ci, vp, tp, vp]
     lib.harris_plan.argtypes = [ci, ci, ci, ci, ci, ci, tp, tp, ctypes.POINTER(ctypes.c_longlong)]
-    for name in ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan", "harris_version"):
+    lib.harris_coarsity_grouped.argtypes = [vp, ci, ci, ci, ci, cf, cf, ci, ci, vp, ctypes.c_longlong, vp, vp]
+    lib.harris_grouped_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.harris_grouped_workspace_bytes.restype = ctypes.c_longlong
+    for name in ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan", "harris_version",
+                 "harris_coarsity_grouped"):
         getattr(lib, name).restype = ci
     lib.harris_strerror.argtypes = [ci]
     lib.harris_strerror.restype = ctypes.c_char_p
@@ -151,6 +155,30 @@ def harris_coarsity_ex(rgb, k: float = 0.04, sobel_scale: float = 1.0, window: i
     with torch.cuda.device(rgb.device):
         _check(load_library().harris_coarsity_ex(rgb.data_ptr(), dtype, B, H, W, k, sobel_scale, window,
                                                  out.data_ptr(), _tuning_arg(tuning), _stream_ptr(stream, rgb.device)))
+    return out
+
+
+def harris_grouped_workspace_bytes(grouping: int, batch: int, H: int, W: int) -> int:
+    return int(load_library().harris_grouped_workspace_bytes(grouping, batch, H, W))
+
+
+def harris_coarsity_grouped(rgb, k: float = 0.04, sobel_scale: float = 1.0, window: int = HARRIS_WINDOW_BOX,
+                            grouping: int = 1, workspace=None, out=None, stream=None):
+    """The unfused / partly fused kernel groupings; `workspace` is a float32 device tensor (made here if None)."""
+    import torch
+    if not isinstance(rgb, torch.Tensor) or rgb.dtype not in (torch.float32, torch.uint8):
+        raise TypeError("rgb must be a float32 or uint8 torch tensor")
+    B, H, W, out = _prepare(rgb, out, rgb.dtype)
+    need = harris_grouped_workspace_bytes(grouping, B, H, W)
+    if need < 0:
+        raise HarrisError(-3, harris_strerror(-3))
+    if workspace is None:
+        workspace = torch.empty(max(1, need // 4), dtype=torch.float32, device=rgb.device)
+    dtype = HARRIS_U8 if rgb.dtype == torch.uint8 else HARRIS_F32
+    with torch.cuda.device(rgb.device):
+        _check(load_library().harris_coarsity_grouped(rgb.data_ptr(), dtype, B, H, W, k, sobel_scale, window, grouping,
+                                                      workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                                      out.data_ptr(), _stream_ptr(stream, rgb.device)))
     return out
 
 

@@ -9,7 +9,7 @@
 
 namespace {
 
-constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVersion = 200;   // 0.2.0
 
 bool power_of_two_aligned(uintptr_t p, unsigned bytes) { return (p & (uintptr_t)(bytes - 1)) == 0; }
 
@@ -201,12 +201,35 @@ int harris_coarsity_u8(const uint8_t* rgb, int batch, int H, int W, float k, flo
     return harris_coarsity_ex(rgb, HARRIS_U8, batch, H, W, k, 1.0f, HARRIS_WINDOW_BOX, out, nullptr, stream);
 }
 
+long long harris_grouped_workspace_bytes(int grouping, int batch, int H, int W) {
+    if (grouping < 1 || grouping > 4 || batch < 0 || H < 4 || W < 4) return -1;
+    return (long long)(harris_launch::grouped_workspace_floats(grouping, batch, H, W) * sizeof(float));
+}
+
+int harris_coarsity_grouped(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale,
+                            int window, int grouping, void* workspace, long long workspace_bytes,
+                            float* out, void* stream) {
+    if (grouping < 1 || grouping > 4) return HARRIS_ERR_ARG;
+    if (grouping == 4) return harris_coarsity_ex(rgb, dtype, batch, H, W, k, sobel_scale, window, out, nullptr, stream);
+    if (dtype != HARRIS_F32 && dtype != HARRIS_U8) return HARRIS_ERR_ARG;
+    if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
+    if (!isfinite(k) || !isfinite(sobel_scale)) return HARRIS_ERR_ARG;
+    if (window != HARRIS_WINDOW_BOX && window != HARRIS_WINDOW_BINOMIAL) return HARRIS_ERR_ARG;
+    if (batch == 0 || H == 4 || W == 4) return HARRIS_OK;
+    if (rgb == nullptr || out == nullptr || workspace == nullptr) return HARRIS_ERR_NULL;
+    if (pointer_alignment(out) < 4 || pointer_alignment(workspace) < 4) return HARRIS_ERR_ARG;
+    if (dtype == HARRIS_F32 && pointer_alignment(rgb) < 4) return HARRIS_ERR_ARG;
+    if (workspace_bytes < harris_grouped_workspace_bytes(grouping, batch, H, W)) return HARRIS_ERR_ARG;
+    return harris_launch::launch_grouped(rgb, dtype, batch, H, W, k, sobel_scale, window == HARRIS_WINDOW_BINOMIAL,
+                                         grouping, static_cast<float*>(workspace), out, stream);
+}
+
 const char* harris_strerror(int status) {
     switch (status) {
         case HARRIS_OK: return "success";
         case HARRIS_ERR_NULL: return "rgb or out is NULL for a non-empty result";
         case HARRIS_ERR_SHAPE: return "invalid shape: batch < 0, H < 4, W < 4, or too many tiles";
-        case HARRIS_ERR_ARG: return "invalid argument: non-finite k or sobel_scale, misaligned pointer, unknown dtype, window or tuning";
+        case HARRIS_ERR_ARG: return "invalid argument: non-finite k or sobel_scale, misaligned pointer, unknown dtype, window, grouping or tuning, workspace too small";
         case HARRIS_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
         default: return "unknown harris_status";
     }

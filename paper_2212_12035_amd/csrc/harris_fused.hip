@@ -289,7 +289,8 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
     // strip so that all wavefronts carry the same load); the lanes beyond only supply halo.
     const unsigned col = (unsigned)strip * p.strip_pitch + lane * PX; // first column of this lane (input and result)
     const unsigned lcol = min(col, (unsigned)(p.W - PX));       // loads stay inside the row
-    const uint32_t load_voff = lcol * (uint32_t)sizeof(In);
+    // Lanes beyond the strip's columns and its 4-column halo request nothing (out-of-range offset).
+    const uint32_t load_voff = lane * PX < p.strip_pitch + 4 ? lcol * (uint32_t)sizeof(In) : 0x80000000u;
     // Halo-only lanes store nothing: an offset beyond any row.  Lanes whose columns lie
     // right of the result row are dropped by the buffer's range check.
     const uint32_t store_voff = lane * PX < p.strip_pitch ? col * 4u : 0x80000000u;
@@ -386,7 +387,8 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 
     const unsigned col = (unsigned)strip * p.strip_pitch + lane * PX;
     const unsigned lcol = min(col, (unsigned)(p.W - PX));
-    const uint32_t load_voff = lcol * (uint32_t)sizeof(In);
+    // Lanes beyond the strip's columns and its 4-column halo request nothing (out-of-range offset).
+    const uint32_t load_voff = lane * PX < p.strip_pitch + 4 ? lcol * (uint32_t)sizeof(In) : 0x80000000u;
     const uint32_t store_voff = lane * PX < p.strip_pitch ? col * 4u : 0x80000000u;
     const uint32_t in_row_bytes = (uint32_t)p.W * (uint32_t)sizeof(In);
     const uint32_t out_row_bytes = (uint32_t)p.m * 4u;

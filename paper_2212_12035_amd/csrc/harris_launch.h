@@ -2,6 +2,8 @@
 #ifndef HARRIS_LAUNCH_H
 #define HARRIS_LAUNCH_H
 
+#include <stddef.h>
+
 #include "harris.h"
 
 namespace harris_launch {
@@ -32,6 +34,13 @@ struct Params {
 // Enqueue the fused kernel.  `shape` must come from harris_plan (all fields set).
 // Returns a harris_status.
 int launch(const Params& p, const harris_tuning& shape, long long n_blocks, int dtype, void* stream);
+
+// Floats of workspace the grouped (unfused) pipelines need; 0 for an unknown grouping.
+size_t grouped_workspace_floats(int grouping, int batch, int H, int W);
+
+// Enqueue grouping 1, 2 or 3 (see harris_coarsity_grouped).  Returns a harris_status.
+int launch_grouped(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale, int binomial,
+                   int grouping, float* workspace, float* out, void* stream);
 
 }  // namespace harris_launch
 

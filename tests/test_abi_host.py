@@ -132,6 +132,24 @@ def test_entry_points_validate_before_touching_the_device(pkg):
     assert lib.harris_coarsity_u8(None, 3, 64, 4, 0.04, None, None) == 0
 
 
+def test_grouped_workspace_sizes_and_validation(pkg):
+    lib = pkg.load_library()
+    H, W = 10, 12
+    n0, n2, n4 = H * W, (H - 2) * (W - 2), (H - 4) * (W - 4)
+    assert pkg.harris_grouped_workspace_bytes(1, 2, H, W) == 4 * 2 * (n0 + 5 * n2 + 3 * n4)
+    assert pkg.harris_grouped_workspace_bytes(2, 2, H, W) == 4 * 2 * (n0 + 3 * n2)
+    assert pkg.harris_grouped_workspace_bytes(3, 2, H, W) == 4 * 2 * (n0 + 2 * n2)
+    assert pkg.harris_grouped_workspace_bytes(4, 2, H, W) == 0
+    assert pkg.harris_grouped_workspace_bytes(5, 2, H, W) == -1 and pkg.harris_grouped_workspace_bytes(1, 2, 3, W) == -1
+    one = ctypes.c_void_p(4096)
+    need = pkg.harris_grouped_workspace_bytes(1, 1, H, W)
+    assert lib.harris_coarsity_grouped(one, 0, 1, H, W, 0.04, 1.0, 0, 0, one, need, one, None) == -3      # grouping 0
+    assert lib.harris_coarsity_grouped(one, 0, 1, H, W, 0.04, 1.0, 0, 1, one, need - 4, one, None) == -3  # workspace too small
+    assert lib.harris_coarsity_grouped(one, 0, 1, H, W, 0.04, 1.0, 0, 1, None, need, one, None) == -1
+    assert lib.harris_coarsity_grouped(one, 0, 1, 3, W, 0.04, 1.0, 0, 2, one, need, one, None) == -2
+    assert lib.harris_coarsity_grouped(None, 0, 0, H, W, 0.04, 1.0, 0, 3, None, 0, None, None) == 0
+
+
 def test_binding_refuses_host_tensors(pkg):
     import torch
     with pytest.raises(TypeError):

@@ -218,6 +218,32 @@ def test_reduced_workloads_all_recipes(gpu, oracle):
         check(run_gpu(gpu, rgb, k=K), oracle.harris(rgb, K, nthreads=4))
 
 
+# ---------------------------------------------------------------- unfused kernel groupings (baselines)
+
+@pytest.mark.parametrize("grouping", [1, 2, 3, 4])
+def test_kernel_groupings_match_the_oracle(gpu, oracle, grouping):
+    import torch
+    for rgb, scale, window, k in ((hi.rectangles_f32(41, 3, 70, 150), 1.0, 0, K), (hi.white_noise_u8(42, 2, 33, 67), S12, 1, 0.06),
+                                  (hi.white_noise_f32(43, 1, 5, 5), 1.0, 0, K)):
+        say("case grouping %d %s %s scale=%g window=%d" % (grouping, rgb.dtype, rgb.shape, scale, window))
+        out = gpu.harris_coarsity_grouped(torch.from_numpy(rgb).cuda(), k, scale, window, grouping)
+        torch.cuda.synchronize()
+        check(out.cpu().numpy(), oracle.harris(rgb, k, scale, window))
+
+
+def test_groupings_agree_with_the_fused_kernel_at_full_size(gpu):
+    import torch
+    rgb = torch.from_numpy(hi.make("noise_f32_1536x2560")).cuda()
+    say("case groupings vs fused, full 1536x2560")
+    fused = gpu.harris_coarsity(rgb, K)
+    ws = torch.empty(gpu.harris_grouped_workspace_bytes(1, 1, 1536, 2560) // 4, device="cuda")
+    for grouping in (1, 2, 3):
+        other = gpu.harris_coarsity_grouped(rgb, K, grouping=grouping, workspace=ws)
+        torch.cuda.synchronize()
+        scale = float(fused.abs().max())
+        assert float((other - fused).abs().max()) <= 1e-4 * scale + 1e-6
+
+
 # ---------------------------------------------------------------- degenerate inputs and closed forms on the GPU
 
 def test_constant_image_gives_exact_zero(gpu):
