@@ -43,7 +43,8 @@ extern "C" {
 typedef enum harris_status {
     HARRIS_OK = 0,
     HARRIS_ERR_NULL = -1,    /* rgb or out is NULL although the result is not empty        */
-    HARRIS_ERR_SHAPE = -2,   /* batch < 0, H < 4, W < 4, W > 2^28, or more than 2^31-1 tiles   */
+    HARRIS_ERR_SHAPE = -2,   /* batch < 0, H < 4, W < 4, W > 2^28, more than 2^31-1 tiles, or
+                                pitches smaller than the image                               */
     HARRIS_ERR_ARG = -3,     /* k or sobel_scale not finite, unknown dtype/window/tuning    */
     HARRIS_ERR_LAUNCH = -4   /* the HIP runtime refused the kernel launch                   */
 } harris_status;
@@ -127,6 +128,31 @@ int harris_coarsity_u8(const uint8_t* rgb, int batch, int H, int W, float k, flo
  */
 int harris_coarsity_ex(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale,
                        int window, float* out, const harris_tuning* tuning, void* stream);
+
+/*
+ * Distances between rows, planes and images, for images that are not dense: padded
+ * rows (the thesis rounds rows up to the vector width, section 4.3 "Vectorisation"), a
+ * region of interest inside a larger image, planes or images kept apart.  Element
+ * (h, w) of plane c of image b is at rgb[b*rgb_image_pitch + c*rgb_plane_pitch +
+ * h*rgb_row_pitch + w] (in input elements) and result (y, x) of image b at
+ * out[b*out_image_pitch + y*out_row_pitch + x] (in floats).  Requirements, else
+ * HARRIS_ERR_SHAPE: rgb_row_pitch >= W, rgb_plane_pitch >= (H-1)*rgb_row_pitch + W,
+ * rgb_image_pitch >= 2*rgb_plane_pitch + (H-1)*rgb_row_pitch + W, out_row_pitch >= W-4,
+ * out_image_pitch >= (H-5)*out_row_pitch + W-4.  Padding is never read or written.
+ */
+typedef struct harris_layout {
+    long long rgb_row_pitch, rgb_plane_pitch, rgb_image_pitch;
+    long long out_row_pitch, out_image_pitch;
+} harris_layout;
+
+/*
+ * harris_coarsity_ex for pitched images.  layout == NULL means dense.  The widest lane
+ * width is taken that the base pointers and all pitches allow (16-byte multiples for
+ * the fastest path); `tuning` as in harris_coarsity_ex.
+ */
+int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
+                            float k, float sobel_scale, int window, float* out,
+                            const harris_tuning* tuning, void* stream);
 
 /*
  * The launch shape harris_coarsity_ex would use for this problem (after applying

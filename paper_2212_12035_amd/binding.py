@@ -20,7 +20,8 @@ _LIB_PATH = os.path.join(_HERE, "libharris.so")
 
 #: every symbol include/harris.h declares
 EXPORTS = ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan",
-           "harris_coarsity_grouped", "harris_grouped_workspace_bytes", "harris_strerror", "harris_version")
+           "harris_coarsity_pitched", "harris_coarsity_grouped", "harris_grouped_workspace_bytes",
+           "harris_strerror", "harris_version")
 
 
 class HarrisError(RuntimeError):
@@ -29,6 +30,13 @@ class HarrisError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__("libharris: %s (status %d)" % (message, status))
         self.status = status
+
+
+class HarrisLayout(ctypes.Structure):
+    """Mirror of `harris_layout`: pitches in elements."""
+    _fields_ = [("rgb_row_pitch", ctypes.c_longlong), ("rgb_plane_pitch", ctypes.c_longlong),
+                ("rgb_image_pitch", ctypes.c_longlong), ("out_row_pitch", ctypes.c_longlong),
+                ("out_image_pitch", ctypes.c_longlong)]
 
 
 class HarrisTuning(ctypes.Structure):
@@ -64,6 +72,8 @@ def load_library() -> ctypes.CDLL:
     lib.harris_coarsity_u8.argtypes = [vp, ci, ci, ci, cf, vp, vp]
     lib.harris_coarsity_ex.argtypes = [vp, ci, ci, ci, ci, cf, cf, ci, vp, tp, vp]
     lib.harris_plan.argtypes = [ci, ci, ci, ci, ci, ci, tp, tp, ctypes.POINTER(ctypes.c_longlong)]
+    lib.harris_coarsity_pitched.argtypes = [vp, ci, ci, ci, ci, ctypes.POINTER(HarrisLayout), cf, cf, ci, vp, tp, vp]
+    lib.harris_coarsity_pitched.restype = ci
     lib.harris_coarsity_grouped.argtypes = [vp, ci, ci, ci, ci, cf, cf, ci, ci, vp, ctypes.c_longlong, vp, vp]
     lib.harris_grouped_workspace_bytes.argtypes = [ci, ci, ci, ci]
     lib.harris_grouped_workspace_bytes.restype = ctypes.c_longlong
@@ -155,6 +165,32 @@ def harris_coarsity_ex(rgb, k: float = 0.04, sobel_scale: float = 1.0, window: i
     with torch.cuda.device(rgb.device):
         _check(load_library().harris_coarsity_ex(rgb.data_ptr(), dtype, B, H, W, k, sobel_scale, window,
                                                  out.data_ptr(), _tuning_arg(tuning), _stream_ptr(stream, rgb.device)))
+    return out
+
+
+def harris_coarsity_pitched(rgb, out, k: float = 0.04, sobel_scale: float = 1.0, window: int = HARRIS_WINDOW_BOX,
+                            tuning=None, stream=None):
+    """General form for strided tensors: rgb [batch][3][H][W] and out [batch][H-4][W-4] may be views
+    (padded rows, a region of interest, a slice of planes) as long as the last stride is 1 and the
+    other strides are non-negative; the pitches are taken from the tensors' strides."""
+    import torch
+    if (not isinstance(rgb, torch.Tensor) or rgb.device.type != "cuda" or rgb.dtype not in (torch.float32, torch.uint8)
+            or rgb.dim() != 4 or rgb.shape[1] != 3):
+        raise TypeError("rgb must be a float32 or uint8 ROCm tensor of shape [batch][3][H][W]")
+    B, _, H, W = rgb.shape
+    if H < 4 or W < 4:
+        raise HarrisError(-2, harris_strerror(-2))
+    if (not isinstance(out, torch.Tensor) or out.device != rgb.device or out.dtype != torch.float32
+            or tuple(out.shape) != (B, H - 4, W - 4)):
+        raise ValueError("out must be a float32 tensor [batch][H-4][W-4] on rgb's device")
+    if (W > 1 and rgb.stride(3) != 1) or (W - 4 > 1 and out.stride(2) != 1):
+        raise ValueError("the last dimension of rgb and out must have stride 1")
+    lay = HarrisLayout(rgb.stride(2) if H > 1 else W, rgb.stride(1), rgb.stride(0) if B > 1 else 3 * rgb.stride(1),
+                       out.stride(1) if H - 4 > 1 else max(W - 4, 1), out.stride(0) if B > 1 else max(1, (H - 4) * out.stride(1)))
+    dtype = HARRIS_U8 if rgb.dtype == torch.uint8 else HARRIS_F32
+    with torch.cuda.device(rgb.device):
+        _check(load_library().harris_coarsity_pitched(rgb.data_ptr(), dtype, B, H, W, ctypes.byref(lay), k, sobel_scale, window,
+                                                      out.data_ptr(), _tuning_arg(tuning), _stream_ptr(stream, rgb.device)))
     return out
 
 

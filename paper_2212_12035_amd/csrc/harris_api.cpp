@@ -161,27 +161,60 @@ int harris_plan(int dtype, int batch, int H, int W, int rgb_align, int out_align
     return plan(dtype, batch, H, W, rgb_align, out_align, tuning, chosen, n_blocks, nullptr);
 }
 
-int harris_coarsity_ex(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale,
-                       int window, float* out, const harris_tuning* tuning, void* stream) {
+int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
+                            float k, float sobel_scale, int window, float* out,
+                            const harris_tuning* tuning, void* stream) {
     if (dtype != HARRIS_F32 && dtype != HARRIS_U8) return HARRIS_ERR_ARG;
     if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
     if (!isfinite(k) || !isfinite(sobel_scale)) return HARRIS_ERR_ARG;
     if (window != HARRIS_WINDOW_BOX && window != HARRIS_WINDOW_BINOMIAL) return HARRIS_ERR_ARG;
+    const long long n = H - 4, m = W - 4;
+    harris_layout lay;
+    if (layout) {
+        lay = *layout;
+    } else {
+        lay.rgb_row_pitch = W; lay.rgb_plane_pitch = (long long)H * W; lay.rgb_image_pitch = 3LL * H * W;
+        lay.out_row_pitch = m; lay.out_image_pitch = n * m;
+    }
+    const long long in_rows_span = (long long)(H - 1) * lay.rgb_row_pitch + W;
+    if (lay.rgb_row_pitch < W || lay.rgb_plane_pitch < in_rows_span || lay.rgb_image_pitch < 2 * lay.rgb_plane_pitch + in_rows_span)
+        return HARRIS_ERR_SHAPE;
+    if (lay.out_row_pitch < m || (n > 0 && lay.out_image_pitch < (n - 1) * lay.out_row_pitch + m)) return HARRIS_ERR_SHAPE;
     const bool empty = batch == 0 || H == 4 || W == 4;
     if (!empty && (rgb == nullptr || out == nullptr)) return HARRIS_ERR_NULL;
     if (!empty && pointer_alignment(out) < 4) return HARRIS_ERR_ARG;
     if (!empty && dtype == HARRIS_F32 && pointer_alignment(rgb) < 4) return HARRIS_ERR_ARG;
 
+    // Alignment that every row start shares: the base pointer's and each pitch's (in bytes).
+    auto common_alignment = [](unsigned a, long long pitch_bytes) {
+        while (a > 1 && pitch_bytes % a != 0) a /= 2;
+        return a;
+    };
+    unsigned rgb_align = 16, out_align = 16;
+    if (!empty) {
+        const long long e = elem_size(dtype);
+        rgb_align = pointer_alignment(rgb);
+        if (rgb_align > 16) rgb_align = 16;
+        rgb_align = common_alignment(rgb_align, lay.rgb_row_pitch * e);
+        rgb_align = common_alignment(rgb_align, lay.rgb_plane_pitch * e);
+        rgb_align = common_alignment(rgb_align, lay.rgb_image_pitch * e);
+        out_align = pointer_alignment(out);
+        if (out_align > 16) out_align = 16;
+        out_align = common_alignment(out_align, lay.out_row_pitch * 4);
+        out_align = common_alignment(out_align, lay.out_image_pitch * 4);
+    }
+
     harris_launch::Params p;
     harris_tuning shape;
     long long n_blocks = 0;
-    int rc = plan(dtype, batch, H, W, empty ? 16 : (int)pointer_alignment(rgb), empty ? 16 : (int)pointer_alignment(out),
-                  tuning, &shape, &n_blocks, &p);
+    int rc = plan(dtype, batch, H, W, (int)rgb_align, (int)out_align, tuning, &shape, &n_blocks, &p);
     if (rc != HARRIS_OK) return rc;
     if (empty) return HARRIS_OK;
 
     p.rgb = rgb;
     p.out = out;
+    p.in_row_pitch = lay.rgb_row_pitch; p.in_plane_pitch = lay.rgb_plane_pitch; p.in_image_pitch = lay.rgb_image_pitch;
+    p.out_row_pitch = lay.out_row_pitch; p.out_image_pitch = lay.out_image_pitch;
     // The Sobel scale multiplies Ix and Iy, which are linear in gray: fold it (and the
     // 1/255 of 8-bit input) into the three gray weights.
     const float in_scale = dtype == HARRIS_U8 ? sobel_scale / 255.0f : sobel_scale;
@@ -191,6 +224,11 @@ int harris_coarsity_ex(const void* rgb, int dtype, int batch, int H, int W, floa
     p.k = k;
     p.binomial = window == HARRIS_WINDOW_BINOMIAL ? 1 : 0;
     return harris_launch::launch(p, shape, n_blocks, dtype, stream);
+}
+
+int harris_coarsity_ex(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale,
+                       int window, float* out, const harris_tuning* tuning, void* stream) {
+    return harris_coarsity_pitched(rgb, dtype, batch, H, W, nullptr, k, sobel_scale, window, out, tuning, stream);
 }
 
 int harris_coarsity(const float* rgb, int batch, int H, int W, float k, float* out, void* stream) {
@@ -228,7 +266,7 @@ const char* harris_strerror(int status) {
     switch (status) {
         case HARRIS_OK: return "success";
         case HARRIS_ERR_NULL: return "rgb or out is NULL for a non-empty result";
-        case HARRIS_ERR_SHAPE: return "invalid shape: batch < 0, H < 4, W < 4, or too many tiles";
+        case HARRIS_ERR_SHAPE: return "invalid shape: batch < 0, H < 4, W < 4, too many tiles, or pitches smaller than the image";
         case HARRIS_ERR_ARG: return "invalid argument: non-finite k or sobel_scale, misaligned pointer, unknown dtype, window, grouping or tuning, workspace too small";
         case HARRIS_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
         default: return "unknown harris_status";

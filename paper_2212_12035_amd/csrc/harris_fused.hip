@@ -297,9 +297,9 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
     const uint32_t in_row_bytes = (uint32_t)p.W * (uint32_t)sizeof(In);
     const uint32_t out_row_bytes = (uint32_t)p.m * 4u;
 
-    const size_t plane = (size_t)p.H * p.W;
-    const In* img_in = static_cast<const In*>(p.rgb) + (size_t)img * 3 * plane;
-    float* img_out = p.out + (size_t)img * p.n * p.m;
+    const size_t plane = (size_t)p.in_plane_pitch;
+    const In* img_in = static_cast<const In*>(p.rgb) + (size_t)img * (size_t)p.in_image_pitch;
+    float* img_out = p.out + (size_t)img * (size_t)p.out_image_pitch;
 
     // Input row read at step t.  Steps past the band's end (the loop runs in trips of U
     // steps, and the queue reads D rows ahead) get an empty descriptor: such a load
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
     auto in_row_ptr = [&](int t) -> const In* {
         int r = up ? y0 + rows + 3 - t : y0 + t;
         r = max(0, min(p.H - 1, r));
-        return img_in + (size_t)r * p.W;
+        return img_in + (size_t)r * (size_t)p.in_row_pitch;
     };
     auto in_row_size = [&](int t) -> uint32_t { return t < steps ? in_row_bytes : 0u; };
 
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
             // Result row: the top row of the 5-row window that this step completes.  Steps
             // past the band's end get an empty descriptor and store nothing.
             const int orow = max(0, min(p.n - 1, up ? y0 + rows + 3 - t : y0 + t - 4));
-            const __amdgpu_buffer_rsrc_t out_rs = make_rsrc(img_out + (size_t)orow * p.m, t < steps ? out_row_bytes : 0u);
+            const __amdgpu_buffer_rsrc_t out_rs = make_rsrc(img_out + (size_t)orow * (size_t)p.out_row_pitch, t < steps ? out_row_bytes : 0u);
             row_step<2, (4 + u) % 3, PX, BINOM>(lb, gc, p.k, out_rs, store_voff);
         });
     }
@@ -393,16 +393,16 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
     const uint32_t in_row_bytes = (uint32_t)p.W * (uint32_t)sizeof(In);
     const uint32_t out_row_bytes = (uint32_t)p.m * 4u;
 
-    const size_t plane = (size_t)p.H * p.W;
-    const In* img_in = static_cast<const In*>(p.rgb) + (size_t)img * 3 * plane;
-    float* img_out = p.out + (size_t)img * p.n * p.m;
+    const size_t plane = (size_t)p.in_plane_pitch;
+    const In* img_in = static_cast<const In*>(p.rgb) + (size_t)img * (size_t)p.in_image_pitch;
+    float* img_out = p.out + (size_t)img * (size_t)p.out_image_pitch;
 
     // All RW rows of this wavefront at once; rows below the image get an empty descriptor.
     RawRow<In, PX> raw[RW];
     static_for<0, RW>([&](auto tt) {
         constexpr int t = decltype(tt)::value;
         const int r = y_wave + t;
-        load_row<In, PX, LAUX>(raw[t], img_in + (size_t)min(r, p.H - 1) * p.W, plane, r < p.H ? in_row_bytes : 0u, load_voff);
+        load_row<In, PX, LAUX>(raw[t], img_in + (size_t)min(r, p.H - 1) * (size_t)p.in_row_pitch, plane, r < p.H ? in_row_bytes : 0u, load_voff);
     });
     __builtin_amdgcn_sched_barrier(0);
 
@@ -411,7 +411,7 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
     float* my_halo = halo_lds + ((size_t)wave * 4 * kWave + lane) * PX;
     auto out_desc = [&](int t) {   // result row completed by step t (t >= 4)
         const int orow = min(p.n - 1, y_wave + t - 4);
-        return make_rsrc(img_out + (size_t)orow * p.m, t - 4 < out_rows ? out_row_bytes : 0u);
+        return make_rsrc(img_out + (size_t)orow * (size_t)p.out_row_pitch, t - 4 < out_rows ? out_row_bytes : 0u);
     };
     const __amdgpu_buffer_rsrc_t no_store = make_rsrc(img_out, 0);
 

@@ -14,8 +14,10 @@ constexpr int valid_lanes(int px) { return 64 - (4 + px - 1) / px; }
 
 // Kernel arguments (passed by value).
 struct Params {
-    const void* rgb;        // device, [batch][3][H][W]
-    float* out;             // device, [batch][n][m]
+    const void* rgb;        // device, [batch][3][H][W] with the pitches below
+    float* out;             // device, [batch][n][m] with the pitches below
+    long long in_row_pitch, in_plane_pitch, in_image_pitch;   // in input elements
+    long long out_row_pitch, out_image_pitch;                 // in floats
     int H, W;               // input rows, columns
     int n, m;               // result rows, columns (H-4, W-4)
     int rows_per_band;      // result rows per band (BANDS) or per tile (TILES)

@@ -150,6 +150,41 @@ def test_grouped_workspace_sizes_and_validation(pkg):
     assert lib.harris_coarsity_grouped(None, 0, 0, H, W, 0.04, 1.0, 0, 3, None, 0, None, None) == 0
 
 
+def test_pitched_entry_validates_the_layout(pkg):
+    lib = pkg.load_library()
+    one = ctypes.c_void_p(4096)
+    H, W = 10, 12
+
+    def call(**kw):
+        lay = dict(rgb_row_pitch=W, rgb_plane_pitch=H * W, rgb_image_pitch=3 * H * W, out_row_pitch=W - 4, out_image_pitch=(H - 4) * (W - 4))
+        lay.update(kw)
+        return lib.harris_coarsity_pitched(one, 0, 2, H, W, ctypes.byref(pkg.HarrisLayout(**lay)), 0.04, 1.0, 0, one, None, None)
+
+    assert call(rgb_row_pitch=W - 1) == -2
+    assert call(rgb_plane_pitch=H * W - 1) == -2
+    assert call(rgb_image_pitch=3 * H * W - 1) == -2
+    assert call(out_row_pitch=W - 5) == -2
+    assert call(out_image_pitch=(H - 4) * (W - 4) - 1) == -2
+    # padded rows need matching plane pitch
+    assert call(rgb_row_pitch=W + 4) == -2
+    # NULL layout means dense: same checks as harris_coarsity_ex
+    assert lib.harris_coarsity_pitched(None, 0, 1, H, W, None, 0.04, 1.0, 0, one, None, None) == -1
+    assert lib.harris_coarsity_pitched(None, 0, 0, H, W, None, 0.04, 1.0, 0, None, None, None) == 0
+
+
+def test_product_sources_never_reach_for_the_oracle():
+    # The oracle is test infrastructure: nothing under the package (or the headers) may name it.
+    pkg_dir = os.path.join(ROOT, "paper_2212_12035_amd")
+    for base, _, files in os.walk(pkg_dir):
+        for name in files:
+            if name.endswith((".py", ".hip", ".cpp", ".h")):
+                text = open(os.path.join(base, name)).read()
+                assert "oracle" not in text.lower(), os.path.join(base, name)
+    assert "oracle" not in open(os.path.join(ROOT, "include", "harris.h")).read().lower()
+    assert "paper_2212_12035_amd" not in open(os.path.join(ROOT, "oracle", "harris_oracle.py")).read()
+    assert "harris.h" not in open(os.path.join(ROOT, "oracle", "harris_ref.cpp")).read()
+
+
 def test_binding_refuses_host_tensors(pkg):
     import torch
     with pytest.raises(TypeError):

@@ -218,6 +218,46 @@ def test_reduced_workloads_all_recipes(gpu, oracle):
         check(run_gpu(gpu, rgb, k=K), oracle.harris(rgb, K, nthreads=4))
 
 
+# ---------------------------------------------------------------- pitched layouts: padded rows, regions of interest
+
+def test_region_of_interest_and_padded_result(gpu, oracle):
+    import torch
+    big = hi.rectangles_f32(51, 2, 120, 340)
+    dev = torch.from_numpy(big).cuda()
+    for (y0, x0, H, W) in ((8, 16, 90, 260), (3, 5, 77, 131), (0, 2, 120, 338), (40, 64, 5, 5)):
+        roi = dev[:, :, y0:y0 + H, x0:x0 + W]                       # a view: pitches of the big image
+        padded = torch.full((2, H - 4 + 3, W - 4 + 7), float("nan"), device="cuda")
+        out = padded[:, 1:1 + H - 4, 4:4 + W - 4]                   # a view into a larger result buffer
+        say("case roi y0=%d x0=%d %dx%d" % (y0, x0, H, W))
+        gpu.harris_coarsity_pitched(roi, out, K)
+        torch.cuda.synchronize()
+        check(out.cpu().numpy(), oracle.harris(np.ascontiguousarray(big[:, :, y0:y0 + H, x0:x0 + W]), K))
+        rest = padded.clone(); rest[:, 1:1 + H - 4, 4:4 + W - 4] = float("nan")
+        assert bool(torch.isnan(rest).all())                         # nothing written outside the view
+
+
+def test_padded_rows_and_separate_planes(gpu, oracle):
+    import torch
+    H, W, pitch = 50, 250, 256                                       # rows rounded up to 256 elements
+    rgb = hi.white_noise_u8(52, 3, H, W)
+    store = torch.zeros((3, 3, H + 2, pitch), dtype=torch.uint8, device="cuda")
+    view = store[:, :, 1:1 + H, :W]
+    view.copy_(torch.from_numpy(rgb).cuda())
+    out = torch.empty((3, H - 4, pitch), device="cuda")[:, :, :W - 4]
+    say("case padded u8 rows")
+    for tune in (None, dict(schedule=1), dict(schedule=2, rows=8, waves_per_block=3)):
+        gpu.harris_coarsity_pitched(view, out, K, S12, 1, tuning=tune)
+        torch.cuda.synchronize()
+        check(out.cpu().numpy(), oracle.harris(rgb, K, S12, 1))
+    f32 = hi.white_noise_f32(53, 2, 41, 260)
+    store = torch.zeros((2, 3, 41, 264), device="cuda")              # 16-byte multiple pitch: widest lanes stay usable
+    store[:, :, :, :260].copy_(torch.from_numpy(f32).cuda())
+    res = torch.empty((2, 37, 256), device="cuda")
+    gpu.harris_coarsity_pitched(store[:, :, :, :260], res, K)
+    torch.cuda.synchronize()
+    check(res.cpu().numpy(), oracle.harris(f32, K))
+
+
 # ---------------------------------------------------------------- unfused kernel groupings (baselines)
 
 @pytest.mark.parametrize("grouping", [1, 2, 3, 4])
