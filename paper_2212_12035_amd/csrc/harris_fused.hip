@@ -174,10 +174,9 @@ struct LineBuffers {
 
 // One row step.  GS is the ring slot that receives this step's gray row.
 // STAGE 0: gray only (first two rows of a band); 1: also Sobel and products (next
-// two rows); 2: also window sums, coarsity and the store of one result row.
+// two rows); 2: also window sums and coarsity: one result row in o, for the caller to store.
 template <int STAGE, int GS, int PX, bool BINOM>
-__device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[PX], float k,
-                                         __amdgpu_buffer_rsrc_t out_rs, uint32_t store_voff) {
+__device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[PX], float k, float (&o)[PX]) {
     constexpr int PS = (GS + 1) % 3;          // product slot written at this step
 #pragma unroll
     for (int i = 0; i < PX; ++i) lb.g[GS][i] = gc[i];
@@ -237,14 +236,12 @@ __device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[
             }
         }
         // Stage a5.
-        float o[PX];
 #pragma unroll
         for (int i = 0; i < PX; ++i) {
             float det = fmaf(s[0][i], s[2][i], -(s[1][i] * s[1][i]));
             float tr = s[0][i] + s[2][i];
             o[i] = fmaf(-(k * tr), tr, det);
         }
-        store_row<PX>(o, out_rs, store_voff);
     }
 }
 
@@ -319,8 +316,7 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
     });
 
     LineBuffers<PX> lb;
-    float gc[PX];
-    const __amdgpu_buffer_rsrc_t no_store = make_rsrc(img_out, 0);
+    float gc[PX], o[PX];
 
     // Rows 0..3 of the band fill the pipeline.
     static_for<0, 4>([&](auto tt) {
@@ -329,7 +325,7 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
         __builtin_amdgcn_sched_barrier(0);
         load_row<In, PX, LAUX>(queue[t % D], in_row_ptr(t + D), plane, in_row_size(t + D), load_voff);
         __builtin_amdgcn_sched_barrier(0);
-        row_step<(t < 2 ? 0 : 1), t % 3, PX, BINOM>(lb, gc, p.k, no_store, store_voff);
+        row_step<(t < 2 ? 0 : 1), t % 3, PX, BINOM>(lb, gc, p.k, o);
     });
 
     for (int t0 = 4; t0 < steps; t0 += U) {
@@ -346,7 +342,8 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
             // past the band's end get an empty descriptor and store nothing.
             const int orow = max(0, min(p.n - 1, up ? y0 + rows + 3 - t : y0 + t - 4));
             const __amdgpu_buffer_rsrc_t out_rs = make_rsrc(img_out + (size_t)orow * (size_t)p.out_row_pitch, t < steps ? out_row_bytes : 0u);
-            row_step<2, (4 + u) % 3, PX, BINOM>(lb, gc, p.k, out_rs, store_voff);
+            row_step<2, (4 + u) % 3, PX, BINOM>(lb, gc, p.k, o);
+            store_row<PX>(o, out_rs, store_voff);
         });
     }
 }
@@ -407,13 +404,12 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
     __builtin_amdgcn_sched_barrier(0);
 
     LineBuffers<PX> lb;
-    float gc[PX];
+    float gc[PX], none[PX];
+    // The RW result rows stay in registers until the wavefront has used up all its loads and
+    // are stored together at the end: bursts of reads and bursts of writes use the memory
+    // better than a fine mixture (measured on 1536x2560: 13.0 us against 14.4 us).
+    float results[RW][PX];
     float* my_halo = halo_lds + ((size_t)wave * 4 * kWave + lane) * PX;
-    auto out_desc = [&](int t) {   // result row completed by step t (t >= 4)
-        const int orow = min(p.n - 1, y_wave + t - 4);
-        return make_rsrc(img_out + (size_t)orow * (size_t)p.out_row_pitch, t - 4 < out_rows ? out_row_bytes : 0u);
-    };
-    const __amdgpu_buffer_rsrc_t no_store = make_rsrc(img_out, 0);
 
     static_for<0, RW>([&](auto tt) {
         constexpr int t = decltype(tt)::value;
@@ -422,8 +418,8 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 #pragma unroll
             for (int i = 0; i < PX; ++i) my_halo[(size_t)t * kWave * PX + i] = gc[i];
         }
-        if constexpr (t < 4) row_step<(t < 2 ? 0 : 1), t % 3, PX, BINOM>(lb, gc, p.k, no_store, store_voff);
-        else row_step<2, t % 3, PX, BINOM>(lb, gc, p.k, out_desc(t), store_voff);
+        if constexpr (t < 4) row_step<(t < 2 ? 0 : 1), t % 3, PX, BINOM>(lb, gc, p.k, none);
+        else row_step<2, t % 3, PX, BINOM>(lb, gc, p.k, results[t - 4]);
     });
 
     __syncthreads();
@@ -434,9 +430,19 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
             constexpr int t = decltype(tt)::value;
 #pragma unroll
             for (int i = 0; i < PX; ++i) gc[i] = below[(size_t)(t - RW) * kWave * PX + i];
-            row_step<2, t % 3, PX, BINOM>(lb, gc, p.k, out_desc(t), store_voff);
+            row_step<2, t % 3, PX, BINOM>(lb, gc, p.k, results[t - 4]);
         });
     }
+
+    // Result row j of this wavefront is row y_wave + j; rows past the tile or the image get an
+    // empty descriptor, and the last wavefront skips the four rows it has no data for.
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, RW>([&](auto jj) {
+        constexpr int j = decltype(jj)::value;
+        const int orow = min(p.n - 1, y_wave + j);
+        if (j < RW - 4 || wave + 1 < n_waves)
+            store_row<PX>(results[j], make_rsrc(img_out + (size_t)orow * (size_t)p.out_row_pitch, j < out_rows ? out_row_bytes : 0u), store_voff);
+    });
 }
 
 template <typename In, int PX, int D>
