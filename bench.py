@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "68929786fb1fc76b577ef10449ba5233c28c6fd1579c6d464fb538d5ba127fd5"
-TRAFFIC_BYTES = {"noise_f32_1536x2560": 65648494, "rects_f32_64x1080x1920": 2196756563}
+TRAFFIC_SOURCES_SHA256 = "791f4f93a98368006a87ce41b5395e53ff4dcf78fec91b8b8240d1374c1dc8bf"
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 65220855, "rects_f32_64x1080x1920": 2168634196}
 
 
 def kernel_sources_sha256():
