@@ -166,6 +166,15 @@ def test_u8_every_kernel_instance(gpu, oracle, px, prefetch):
         check(run_gpu(gpu, rgb, k=K, tuning=tune), want)
 
 
+@pytest.mark.parametrize("batch,H,W", [(1, 4100, 8), (1, 5, 20000), (300, 9, 9), (2, 6, 1025), (1, 2049, 12), (70000 // 1000, 5, 8)])
+def test_extreme_aspect_ratios_and_many_small_images(gpu, oracle, batch, H, W):
+    rgb = hi.white_noise_f32(300 + H + W, batch, H, W)
+    want = oracle.harris(rgb, K, nthreads=4)
+    for tune in (None, dict(schedule=1), dict(schedule=2, rows=8, waves_per_block=16), dict(schedule=1, rows=64, prefetch=6, waves_per_block=4)):
+        say("case extreme %dx3x%dx%d %s" % (batch, H, W, tune))
+        check(run_gpu(gpu, rgb, k=K, tuning=tune), want)
+
+
 def test_misaligned_base_pointers_take_the_narrow_paths(gpu, oracle):
     import torch
     H, W = 21, 300
