@@ -197,7 +197,7 @@ def main():
 
     achieved = algo_bytes / (launch_us * 1e-6) / 1e9
     result = {
-        "metric": "harris_coarsity_throughput",
+        "metric": "harris_mpixels_per_s",
         "value": round(pixels / (ms_per_step * 1e-3) / 1e6, 1),
         "unit": "Mpixels/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
