@@ -101,6 +101,13 @@ typedef struct harris_tuning {
 #define HARRIS_TUNE_CACHED_LOADS 4u  /* load input rows with the default cache policy             */
 #define HARRIS_TUNE_STREAM_LOADS 8u  /* load input rows non-temporal.  With neither bit the library
                                         decides from the size of the problem                        */
+#define HARRIS_TUNE_ALIGNED_STORES 16u /* TILES with px = 4 only: in every result row the border between
+                                        two strips is moved right to the next 64-byte boundary of the
+                                        row's address, so that no 64-byte block of the result is
+                                        written by two wavefronts; strips are then at most 240
+                                        columns wide instead of 252                                 */
+#define HARRIS_TUNE_PLAIN_STORES 32u /* strips end at the same column in every row.  With neither bit
+                                        the library decides                                         */
 
 /*
  * Harris coarsity of float32 images with the integer Sobel matrices

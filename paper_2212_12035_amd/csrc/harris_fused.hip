@@ -252,7 +252,7 @@ __device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[
 // run of workgroup-sized tile groups.
 __device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned nb) {
     const unsigned q = nb / 8, r = nb % 8, x = b % 8, j = b / 8;
-    return x < r ? x * (q + 1) + j : r * (q + 1) + (x - r) * q + j;
+    return x * q + min(x, r) + j;       // XCDs 0..r-1 take q + 1 groups each, the others q
 }
 
 template <typename In, int PX, int D, int LAUX, bool BINOM>
@@ -263,7 +263,7 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
     const unsigned wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const unsigned waves_per_block = blockDim.x / kWave;
     unsigned blk = blockIdx.x;
-    if (!(p.flags & HARRIS_TUNE_NO_XCD_REMAP)) blk = xcd_contiguous(blk, gridDim.x);
+    blk = (p.flags & HARRIS_TUNE_NO_XCD_REMAP) ? blk : xcd_contiguous(blk, p.n_blocks);
 
     // A workgroup of 2 or 4 wavefronts holds two vertically adjacent bands (of one strip,
     // or of two adjacent strips): band 2j walks upwards and band 2j+1 downwards, so both
@@ -367,15 +367,20 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 
     const unsigned lane = threadIdx.x % kWave;
     const unsigned wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const unsigned n_waves = blockDim.x / kWave;
+    const unsigned n_waves = p.waves_per_block;                 // == blockDim.x / 64
     unsigned tile = blockIdx.x;
-    if (!(p.flags & HARRIS_TUNE_NO_XCD_REMAP)) tile = xcd_contiguous(tile, gridDim.x);
-    // gridDim.x == n_tiles: every workgroup has a tile and every wavefront reaches the barrier.
+    // The grid size is read with all other arguments, not in a branch of its own: one wait
+    // for the arguments instead of two before the first load can be issued.
+    unsigned n_blocks = p.n_blocks;
+    asm volatile("" : "+s"(n_blocks));
+    tile = (p.flags & HARRIS_TUNE_NO_XCD_REMAP) ? tile : xcd_contiguous(tile, n_blocks);
+    // The grid has p.n_blocks == n_tiles workgroups: every workgroup has a tile and every
+    // wavefront reaches the barrier.
 
-    const unsigned img = tile / p.tiles_per_image;
-    const unsigned rem = tile % p.tiles_per_image;
-    const int band = (int)(rem / p.n_strips);
-    const int strip = (int)(rem % p.n_strips);
+    const unsigned img = harris_launch::fastdiv(tile, p.by_tiles_per_image);
+    const unsigned rem = tile - img * p.tiles_per_image;
+    const int band = (int)harris_launch::fastdiv(rem, p.by_n_strips);
+    const int strip = (int)(rem - (unsigned)band * p.n_strips);
 
     const int tile_rows = p.rows_per_band;                      // result rows per tile: NW*RW - 4
     const int y_wave = band * tile_rows + (int)wave * RW;       // first input row = first result row of this wavefront
@@ -384,11 +389,15 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 
     const unsigned col = (unsigned)strip * p.strip_pitch + lane * PX;
     const unsigned lcol = min(col, (unsigned)(p.W - PX));
-    // Lanes beyond the strip's columns and its 4-column halo request nothing (out-of-range offset).
-    const uint32_t load_voff = lane * PX < p.strip_pitch + 4 ? lcol * (uint32_t)sizeof(In) : 0x80000000u;
-    const uint32_t store_voff = lane * PX < p.strip_pitch ? col * 4u : 0x80000000u;
+    // With aligned stores the border between this strip and the next lies, in each result row,
+    // on the first 64-byte boundary of that row's address at or after the nominal border: up to
+    // 12 columns further right.  border_mask is 15 (columns per 64 bytes, minus one) or 0.
+    const unsigned border_mask = (p.flags & HARRIS_TUNE_ALIGNED_STORES) ? 15u : 0u;
+    const unsigned x0 = (unsigned)strip * p.strip_pitch;        // first result column of this strip
+    // Lanes beyond the strip's columns, the border's reach and the 4-column halo request nothing
+    // (out-of-range offset).
+    const uint32_t load_voff = lane * PX < p.strip_pitch + 4 + (border_mask & 12u) ? lcol * (uint32_t)sizeof(In) : 0x80000000u;
     const uint32_t in_row_bytes = (uint32_t)p.W * (uint32_t)sizeof(In);
-    const uint32_t out_row_bytes = (uint32_t)p.m * 4u;
 
     const size_t plane = (size_t)p.in_plane_pitch;
     const In* img_in = static_cast<const In*>(p.rgb) + (size_t)img * (size_t)p.in_image_pitch;
@@ -400,6 +409,33 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
         constexpr int t = decltype(tt)::value;
         const int r = y_wave + t;
         load_row<In, PX, LAUX>(raw[t], img_in + (size_t)min(r, p.H - 1) * (size_t)p.in_row_pitch, plane, r < p.H ? in_row_bytes : 0u, load_voff);
+    });
+    __builtin_amdgcn_sched_barrier(0);
+
+    // Descriptors of the RW result rows, worked out while the loads are in flight (scalar
+    // arithmetic that would otherwise sit between the last result and the first store).
+    // Result row j of this wavefront is row y_wave + j; rows past the tile or the image get
+    // an empty descriptor, whose address is never used.  The descriptor covers this strip's
+    // columns [b0, b1) of the row; a lane's offset is relative to b0 and wraps to a huge
+    // value for lanes left of it, so lanes outside store nothing.
+    __amdgpu_buffer_rsrc_t out_rs[RW];
+    uint32_t out_lead[RW];                                      // byte offset of column x0 from column b0 (<= 0, wrapped)
+    // The empty statement makes everything below depend on values defined after the loads:
+    // none of this arithmetic is moved in front of them.
+    unsigned sx0 = x0;
+    int sy = y_wave;
+    asm volatile("" : "+s"(sx0), "+s"(sy) : : "memory");
+    const unsigned sx1 = sx0 + p.strip_pitch;
+    const uintptr_t out_first = reinterpret_cast<uintptr_t>(img_out) + ((size_t)sy * (size_t)p.out_row_pitch) * 4u;
+    static_for<0, RW>([&](auto jj) {
+        constexpr int j = decltype(jj)::value;
+        const uintptr_t row_addr = out_first + (size_t)j * ((size_t)p.out_row_pitch * 4u);
+        const unsigned a = (unsigned)(row_addr >> 2);           // address in floats
+        const unsigned b0 = sx0 == 0 ? 0u : sx0 + ((0u - (a + sx0)) & border_mask);
+        const unsigned b1 = min((unsigned)p.m, sx1 + ((0u - (a + sx1)) & border_mask));
+        const uint32_t bytes = (j < out_rows && b1 > b0) ? (b1 - b0) * 4u : 0u;
+        out_rs[j] = make_rsrc(reinterpret_cast<const float*>(row_addr) + b0, bytes);
+        out_lead[j] = (sx0 - b0) * 4u;
     });
     __builtin_amdgcn_sched_barrier(0);
 
@@ -434,14 +470,12 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
         });
     }
 
-    // Result row j of this wavefront is row y_wave + j; rows past the tile or the image get an
-    // empty descriptor, and the last wavefront skips the four rows it has no data for.
+    // The last wavefront skips the four rows it has no data for.
     __builtin_amdgcn_sched_barrier(0);
+    const uint32_t lane_bytes = lane * PX * 4u;
     static_for<0, RW>([&](auto jj) {
         constexpr int j = decltype(jj)::value;
-        const int orow = min(p.n - 1, y_wave + j);
-        if (j < RW - 4 || wave + 1 < n_waves)
-            store_row<PX>(results[j], make_rsrc(img_out + (size_t)orow * (size_t)p.out_row_pitch, j < out_rows ? out_row_bytes : 0u), store_voff);
+        if (j < RW - 4 || wave + 1 < n_waves) store_row<PX>(results[j], out_rs[j], lane_bytes + out_lead[j]);
     });
 }
 
@@ -519,6 +553,7 @@ hipError_t launch_in(const harris_launch::Params& p, const harris_tuning& t, dim
 namespace harris_launch {
 
 int launch(const Params& p, const harris_tuning& shape, long long n_blocks, int dtype, void* stream) {
+    if (n_blocks != (long long)p.n_blocks || shape.waves_per_block != (int)p.waves_per_block) return HARRIS_ERR_LAUNCH;
     const dim3 grid((unsigned)n_blocks), block((unsigned)(shape.waves_per_block * kWave));
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = dtype == HARRIS_U8 ? launch_in<uint8_t>(p, shape, grid, block, s)

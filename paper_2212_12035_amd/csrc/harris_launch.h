@@ -12,7 +12,39 @@ namespace harris_launch {
 // columns: the remaining lane(s) only supply the 4-column halo to the right.
 constexpr int valid_lanes(int px) { return 64 - (4 + px - 1) / px; }
 
-// Kernel arguments (passed by value).
+// Division of a 32-bit unsigned number by a divisor fixed at launch, as one multiply-high, an
+// addition and two shifts (Granlund and Montgomery, "Division by invariant integers using
+// multiplication", 1994, the unsigned algorithm for a run-time invariant divisor): with
+// l = ceil(log2 d), mul = floor(2^32 (2^l - d) / d) + 1, sh1 = min(l, 1), sh2 = max(l - 1, 0),
+// floor(x / d) = (t + ((x - t) >> sh1)) >> sh2 where t = high word of mul * x.  Exact for every
+// x < 2^32 and 1 <= d < 2^32.  A workgroup decomposes its index with it before its first load
+// (a hardware integer division costs some 25 dependent scalar instructions).
+struct FastDiv {
+    unsigned mul, sh1, sh2;
+};
+
+inline FastDiv make_fastdiv(unsigned d) {
+    FastDiv f;
+    unsigned l = 0;
+    while (l < 32 && (1ull << l) < d) ++l;
+    f.mul = (unsigned)((((1ull << l) - d) << 32) / d + 1);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l < 1 ? 0 : l - 1;
+    return f;
+}
+
+#if defined(__HIPCC__)
+#define HARRIS_HOST_DEVICE __host__ __device__
+#else
+#define HARRIS_HOST_DEVICE
+#endif
+HARRIS_HOST_DEVICE inline unsigned fastdiv(unsigned x, const FastDiv& f) {
+    const unsigned t = (unsigned)(((unsigned long long)f.mul * x) >> 32);
+    return (t + ((x - t) >> f.sh1)) >> f.sh2;
+}
+
+// Kernel arguments (passed by value).  What the tile kernel reads before its first load sits
+// together, so that a few wide scalar loads fetch it at once.
 struct Params {
     const void* rgb;        // device, [batch][3][H][W] with the pitches below
     float* out;             // device, [batch][n][m] with the pitches below
@@ -22,15 +54,18 @@ struct Params {
     int n, m;               // result rows, columns (H-4, W-4)
     int rows_per_band;      // result rows per band (BANDS) or per tile (TILES)
     unsigned n_strips;      // strips per band
-    unsigned strip_pitch;   // result columns per strip (a multiple of px, at most valid_lanes(px)*px)
-    unsigned n_bands;       // bands (BANDS) or tiles down the image (TILES)
+    unsigned strip_pitch;   // result columns per strip (a multiple of px, at most valid_lanes(px)*px; 12 less with aligned stores)
     unsigned tiles_per_image;  // n_bands * n_strips (TILES: one workgroup each)
-    unsigned blocks_x;      // BANDS: workgroups across a row of bands
-    unsigned blocks_per_image;  // BANDS: workgroups per image
+    FastDiv by_tiles_per_image, by_n_strips;   // TILES: division by these two
+    unsigned n_blocks;      // workgroups of the launch (the grid size)
+    unsigned waves_per_block;  // wavefronts per workgroup (the block size / 64)
     float wr, wg, wb;       // gray weights, times the Sobel scale (and 1/255 for 8-bit input)
     float k;                // coarsity constant
-    int binomial;           // 1: window [1 2 1; 2 4 2; 1 2 1], 0: unweighted 3x3 sum
     unsigned flags;         // HARRIS_TUNE_* bits
+    int binomial;           // 1: window [1 2 1; 2 4 2; 1 2 1], 0: unweighted 3x3 sum
+    unsigned n_bands;       // bands (BANDS) or tiles down the image (TILES)
+    unsigned blocks_x;      // BANDS: workgroups across a row of bands
+    unsigned blocks_per_image;  // BANDS: workgroups per image
 };
 
 // Enqueue the fused kernel.  `shape` must come from harris_plan (all fields set).

@@ -52,16 +52,22 @@ def test_plan_picks_widest_vector_path(pkg):
 def test_plan_tile_arithmetic(pkg):
     # 252 result columns per wavefront at px = 4; 2556 columns -> 11 strips; 1532 rows in
     # bands of 16 -> 96 bands; 4 wavefronts per workgroup.
-    t = dict(schedule=pkg.HARRIS_SCHEDULE_BANDS, px=4, rows=16, prefetch=3, waves_per_block=4, flags=pkg.HARRIS_TUNE_STREAM_LOADS)
+    t = dict(schedule=pkg.HARRIS_SCHEDULE_BANDS, px=4, rows=16, prefetch=3, waves_per_block=4, flags=pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES)
     shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=t)
     assert shape == t and blocks == 6 * 48          # 2 strips x 2 bands per workgroup: ceil(11/2) x ceil(96/2)
     shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 3, 9, 9, tuning=dict(schedule=1, px=1, rows=2, prefetch=2, waves_per_block=1, flags=3))
     assert blocks == 3 * 3 * 1
     # tiles: 8 wavefronts x 8 rows give 60 result rows per tile -> 26 tiles down, 11 across,
     # one workgroup each
-    t = dict(schedule=pkg.HARRIS_SCHEDULE_TILES, px=4, rows=8, prefetch=0, waves_per_block=8, flags=pkg.HARRIS_TUNE_CACHED_LOADS)
+    t = dict(schedule=pkg.HARRIS_SCHEDULE_TILES, px=4, rows=8, prefetch=0, waves_per_block=8, flags=pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES)
     shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=t)
     assert shape == t and blocks == 26 * 11
+    # strip borders moved to 64-byte boundaries: strips of at most 240 columns; 4252 columns
+    # take 18 of them instead of 17, 2556 columns still 11
+    aligned = dict(t, flags=pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES)
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=aligned) == (aligned, 26 * 11)
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 4256, tuning=aligned)[1] == 26 * 18
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 4256, tuning=t)[1] == 26 * 17
     # empty results plan to zero workgroups
     assert pkg.harris_plan(pkg.HARRIS_F32, 0, 64, 64)[1] == 0
     assert pkg.harris_plan(pkg.HARRIS_F32, 2, 4, 64)[1] == 0
@@ -72,18 +78,22 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     small, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
     # one tile per CU: 11 strips x 23 tiles of 9 wavefronts x 8 rows (68 result rows) = 253 workgroups
     assert small["schedule"] == pkg.HARRIS_SCHEDULE_TILES and (small["rows"], small["waves_per_block"]) == (8, 9) and blocks == 253
-    assert small["flags"] & pkg.HARRIS_TUNE_STREAM_LOADS and not small["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS
+    assert small["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES
     # beyond one tile per CU: many tiles of 4 wavefronts x 4 rows (12 result rows); cached loads for large float32
     mid, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4256)
-    assert (mid["schedule"], mid["rows"], mid["waves_per_block"]) == (2, 4, 4) and blocks == 17 * 236
-    assert mid["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS
+    assert (mid["schedule"], mid["rows"], mid["waves_per_block"]) == (2, 4, 4) and blocks == 18 * 236
+    assert mid["flags"] == pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES
     big, blocks = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920)
     assert (big["rows"], big["waves_per_block"]) == (4, 4) and big["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS and blocks == 64 * 90 * 8
-    u8, _ = pkg.harris_plan(pkg.HARRIS_U8, 1, 8192, 8192)
-    assert u8["flags"] & pkg.HARRIS_TUNE_STREAM_LOADS
+    # 8-bit input: non-temporal loads; 35 strips of at most 240 columns cover 8188
+    u8, blocks = pkg.harris_plan(pkg.HARRIS_U8, 1, 8192, 8192)
+    assert u8["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES and blocks == 35 * 683
+    # narrower lanes and bands never move strip borders
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 98)[0]["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 96, tuning=dict(schedule=1))[0]["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES
     # an explicit policy is kept
-    kept, _ = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920, tuning=dict(flags=pkg.HARRIS_TUNE_STREAM_LOADS))
-    assert kept["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS
+    kept, _ = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920, tuning=dict(flags=pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES))
+    assert kept["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES
     # asking for bands gives bands: one wavefront per SIMD for small problems, four-wavefront groups for large
     bands, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=dict(schedule=1))
     assert (bands["rows"], bands["prefetch"], bands["waves_per_block"]) == (17, 3, 1) and blocks == 1001
@@ -102,7 +112,7 @@ def test_plan_rejects_bad_arguments(pkg):
         with pytest.raises(E) as e:
             pkg.harris_plan(*args)
         assert e.value.status == status
-    for bad in (dict(px=3), dict(px=4, prefetch=5), dict(schedule=1, px=4, waves_per_block=3), dict(waves_per_block=1), dict(flags=16), dict(flags=12), dict(rows=-1),
+    for bad in (dict(px=3), dict(px=4, prefetch=5), dict(schedule=1, px=4, waves_per_block=3), dict(waves_per_block=1), dict(flags=64), dict(flags=12), dict(flags=48), dict(schedule=1, flags=16), dict(px=2, flags=16), dict(rows=-1),
                 dict(schedule=3), dict(schedule=2, rows=7), dict(schedule=2, px=2, rows=5), dict(schedule=2, waves_per_block=1), dict(schedule=2, waves_per_block=17),
                 dict(schedule=2, prefetch=3), dict(schedule=2, px=8)):
         with pytest.raises(E) as e:
@@ -110,6 +120,18 @@ def test_plan_rejects_bad_arguments(pkg):
         assert e.value.status == -3
     with pytest.raises(E):                          # px = 4 needs W % 4 == 0
         pkg.harris_plan(0, 1, 64, 98, tuning=dict(px=4))
+
+
+def test_index_division_by_multiplication_is_exact(tmp_path):
+    # The tile kernel splits its workgroup index with a multiply-high division whose constants
+    # the host computes; the same header functions are checked here against the hardware division.
+    import subprocess
+    exe = str(tmp_path / "fastdiv_check")
+    subprocess.run(["g++", "-O2", "-std=c++17", "-I" + os.path.join(ROOT, "include"),
+                    "-I" + os.path.join(ROOT, "paper_2212_12035_amd", "csrc"),
+                    os.path.join(ROOT, "tests", "fastdiv_check.cpp"), "-o", exe], check=True)
+    out = subprocess.run([exe], capture_output=True, text=True)
+    assert out.returncode == 0 and out.stdout.startswith("ok "), out.stdout
 
 
 def test_entry_points_validate_before_touching_the_device(pkg):

@@ -206,6 +206,45 @@ def test_misaligned_base_pointers_take_the_narrow_paths(gpu, oracle):
         check(out.cpu().numpy(), oracle.harris(u8, K))
 
 
+@pytest.mark.parametrize("W", [744, 1000, 488])
+def test_strip_borders_on_64_byte_boundaries(gpu, oracle, W):
+    # With px = 4 the tile kernel moves the border between two strips, row by row, to the
+    # next 64-byte boundary of the result row's address.  Where that lies depends on the
+    # base address and the row pitch modulo 16 floats: go through every phase of the base
+    # (offsets of 0, 4, 8, 12 floats from a 64-byte boundary), with dense rows (pitch W-4,
+    # every row another phase) and padded rows, three to five strips (W = 488: 484 = 2 x 240 + 4
+    # columns need a third one) and guard bands all around; the same with fixed borders and
+    # with 8-bit input.
+    import torch
+    H = 29
+    n, m = H - 4, W - 4
+    rgb = hi.white_noise_f32(60 + W, 2, H, W)
+    want = oracle.harris(rgb, K)
+    src = torch.from_numpy(rgb).cuda()
+    u8 = hi.white_noise_u8(61 + W, 2, H, W)
+    want8 = oracle.harris(u8, K)
+    src8 = torch.from_numpy(u8).cuda()
+    for pitch in (m, m + 4, m + 12, ((m + 15) // 16) * 16):
+        for off in (0, 4, 8, 12):
+            flat = torch.full((2 * n * pitch + 64,), float("nan"), device="cuda")
+            assert flat.data_ptr() % 64 == 0
+            view = flat[16 + off:16 + off + 2 * n * pitch].view(2, n, pitch)[:, :, :m]
+            for flags in (gpu.HARRIS_TUNE_ALIGNED_STORES, gpu.HARRIS_TUNE_PLAIN_STORES):
+                for rows, waves in ((4, 4), (8, 3), (5, 2)):
+                    say("case borders W=%d pitch=%d offset=%d flags=%d tile %dx%d" % (W, pitch, off, flags, waves, rows))
+                    flat.fill_(float("nan"))
+                    gpu.harris_coarsity_pitched(src, view, K, tuning=dict(schedule=2, px=4, rows=rows, waves_per_block=waves, flags=flags))
+                    torch.cuda.synchronize()
+                    check(view.cpu().numpy(), want)
+                    rest = flat.clone()
+                    rest[16 + off:16 + off + 2 * n * pitch].view(2, n, pitch)[:, :, :m] = float("nan")
+                    assert bool(torch.isnan(rest).all())             # padding and guard bands untouched
+            say("case borders u8 W=%d pitch=%d offset=%d" % (W, pitch, off))
+            gpu.harris_coarsity_pitched(src8, view, K, tuning=dict(flags=gpu.HARRIS_TUNE_ALIGNED_STORES))
+            torch.cuda.synchronize()
+            check(view.cpu().numpy(), want8)
+
+
 # ---------------------------------------------------------------- operator variants
 
 @pytest.mark.parametrize("scale", [1.0, S12])
