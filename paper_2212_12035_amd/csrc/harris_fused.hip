@@ -456,6 +456,9 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
         }
         if constexpr (t < 4) row_step<(t < 2 ? 0 : 1), t % 3, PX, BINOM>(lb, gc, p.k, none);
         else row_step<2, t % 3, PX, BINOM>(lb, gc, p.k, results[t - 4]);
+        // Each row is worked through as soon as it has arrived: without this the compiler
+        // gathers the arithmetic of all rows behind the wait for the last one.
+        __builtin_amdgcn_sched_barrier(0);
     });
 
     __syncthreads();
