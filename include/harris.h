@@ -101,6 +101,10 @@ typedef struct harris_tuning {
 #define HARRIS_TUNE_CACHED_LOADS 4u  /* load input rows with the default cache policy             */
 #define HARRIS_TUNE_STREAM_LOADS 8u  /* load input rows non-temporal.  With neither bit the library
                                         decides from the size of the problem                        */
+#define HARRIS_TUNE_KEEP_SHARED_ROWS 64u /* TILES with px = 4 and non-temporal loads only: the input rows
+                                        that two vertically adjacent tiles both read (the first and the
+                                        last four of a tile) are loaded with the default policy instead,
+                                        so that the second reader finds them in L2                   */
 #define HARRIS_TUNE_ALIGNED_STORES 16u /* TILES with px = 4 only: in every result row the border between
                                         two strips is moved right to the next 64-byte boundary of the
                                         row's address, so that no 64-byte block of the result is

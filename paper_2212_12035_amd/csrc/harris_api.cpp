@@ -34,8 +34,9 @@ int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const
     harris_tuning t = {0, 0, 0, 0, 0, 0u};
     if (tuning) t = *tuning;
     if (t.flags & ~(HARRIS_TUNE_NO_ALTERNATE | HARRIS_TUNE_NO_XCD_REMAP | HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS |
-                    HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_PLAIN_STORES)) return HARRIS_ERR_ARG;
+                    HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_PLAIN_STORES | HARRIS_TUNE_KEEP_SHARED_ROWS)) return HARRIS_ERR_ARG;
     if ((t.flags & HARRIS_TUNE_CACHED_LOADS) && (t.flags & HARRIS_TUNE_STREAM_LOADS)) return HARRIS_ERR_ARG;
+    if ((t.flags & HARRIS_TUNE_KEEP_SHARED_ROWS) && !(t.flags & HARRIS_TUNE_STREAM_LOADS)) return HARRIS_ERR_ARG;
     if ((t.flags & HARRIS_TUNE_ALIGNED_STORES) && (t.flags & HARRIS_TUNE_PLAIN_STORES)) return HARRIS_ERR_ARG;
     if (t.schedule != 0 && t.schedule != HARRIS_SCHEDULE_BANDS && t.schedule != HARRIS_SCHEDULE_TILES) return HARRIS_ERR_ARG;
 
@@ -52,7 +53,7 @@ int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const
     if (t.schedule == 0) t.schedule = t.px <= 4 && t.prefetch == 0 ? HARRIS_SCHEDULE_TILES : HARRIS_SCHEDULE_BANDS;
     // Strip borders on 64-byte boundaries of the result rows: the tile kernel with 16-byte lanes.
     const bool can_align = t.schedule == HARRIS_SCHEDULE_TILES && t.px == 4;
-    if ((t.flags & HARRIS_TUNE_ALIGNED_STORES) && !can_align) return HARRIS_ERR_ARG;
+    if ((t.flags & (HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_KEEP_SHARED_ROWS)) && !can_align) return HARRIS_ERR_ARG;
     // Measured, moved against fixed borders: 378 against 393 us on 64x1080x1920 float32, 12.5
     // against 12.8 us on 1536x2560, 37.0 against 37.3 us on 2832x4256, 89 against 93 us on
     // 8192x8192 uint8.
@@ -64,15 +65,23 @@ int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const
     const long long n_strips = m > 0 ? (m + max_pitch - 1) / max_pitch : 0;
     const long long pitch = n_strips > 0 ? ((m + n_strips - 1) / n_strips + t.px - 1) / t.px * t.px : max_pitch;
 
-    // Bytes the launch moves.  Measured rule for the load policy: float32 problems beyond about
-    // half the 256 MB last-level cache run faster with default-policy loads (the rows two tiles
-    // share and the line two strips share are then found in the caches), smaller ones and 8-bit
-    // input with non-temporal loads.
+    // Bytes the launch moves.  Measured rule for the load policy of float32 input: up to about half
+    // the 256 MB last-level cache everything is loaded non-temporal; up to about 400 MB non-temporal
+    // except the rows two tiles share, which the default policy keeps in L2 for the second reader
+    // (2832x4256: 34.6 us against 37.1 us all-default and 39.7 us all-non-temporal; 4096x4096:
+    // 49.7 / 53.8 / 54.6 us); beyond that everything with the default policy (64x1080x1920: 379 us
+    // against 380 us mixed and 404 us non-temporal; 8192x8192: 181 / 188 / 214 us).  8-bit input:
+    // non-temporal with the shared rows kept at every size (8192x8192: 91.1 us against 91.8 us
+    // non-temporal and 105 us default; 64x1080x1920: 176 / 181 / 176 us).
     const long long elem = elem_size(dtype);
     const long long footprint = (long long)batch * (3LL * H * W * elem + 4LL * n * m);
-    const bool cached = dtype == HARRIS_F32 && footprint > (128LL << 20);
-    if (!(t.flags & (HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS)))
-        t.flags |= cached ? HARRIS_TUNE_CACHED_LOADS : HARRIS_TUNE_STREAM_LOADS;
+    if (!(t.flags & (HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS))) {
+        if (dtype == HARRIS_F32 && footprint > (400LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
+        else if (dtype == HARRIS_F32 && footprint > (128LL << 20) && can_align) t.flags |= HARRIS_TUNE_STREAM_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS;
+        else if (dtype == HARRIS_F32 && footprint > (128LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
+        else if (dtype == HARRIS_U8 && can_align) t.flags |= HARRIS_TUNE_STREAM_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS;
+        else t.flags |= HARRIS_TUNE_STREAM_LOADS;
+    }
 
     // Default tile shape.  A problem that one pass over the 256 CUs can hold is fastest as one
     // tile per CU: all CUs then carry the same load and finish together (measured on

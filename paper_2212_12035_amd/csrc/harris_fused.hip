@@ -84,6 +84,10 @@ __device__ __forceinline__ void fetch_halo(float (&a)[PX + 2]) {
 // same workgroup.
 constexpr int kAuxDefault = 0;
 constexpr int kAuxNonTemporal = 2;
+// Tile kernel only, not a hardware value: non-temporal, except that the first and the last
+// four input rows of a tile, which the tile above or below reads as well, are loaded with the
+// default policy.
+constexpr int kAuxKeepShared = -1;
 #ifndef HARRIS_STORE_AUX
 #define HARRIS_STORE_AUX kAuxNonTemporal
 #endif
@@ -408,7 +412,15 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
     static_for<0, RW>([&](auto tt) {
         constexpr int t = decltype(tt)::value;
         const int r = y_wave + t;
-        load_row<In, PX, LAUX>(raw[t], img_in + (size_t)min(r, p.H - 1) * (size_t)p.in_row_pitch, plane, r < p.H ? in_row_bytes : 0u, load_voff);
+        const In* row_in = img_in + (size_t)min(r, p.H - 1) * (size_t)p.in_row_pitch;
+        const uint32_t row_bytes = r < p.H ? in_row_bytes : 0u;
+        if constexpr (LAUX == kAuxKeepShared) {
+            const bool shared = (t < 4 && wave == 0) || (t >= RW - 4 && wave + 1 == n_waves);
+            if (shared) load_row<In, PX, kAuxDefault>(raw[t], row_in, plane, row_bytes, load_voff);
+            else load_row<In, PX, kAuxNonTemporal>(raw[t], row_in, plane, row_bytes, load_voff);
+        } else {
+            load_row<In, PX, LAUX>(raw[t], row_in, plane, row_bytes, load_voff);
+        }
     });
     __builtin_amdgcn_sched_barrier(0);
 
@@ -499,6 +511,13 @@ template <typename In, int PX, int RW>
 hipError_t launch_tiles(const harris_launch::Params& p, dim3 grid, dim3 block, hipStream_t stream) {
     const size_t lds = (size_t)(block.x / kWave) * 4 * kWave * PX * sizeof(float);
     const bool cached = p.flags & HARRIS_TUNE_CACHED_LOADS;
+    if constexpr (PX == 4) {
+        if (p.flags & HARRIS_TUNE_KEEP_SHARED_ROWS) {
+            if (p.binomial) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxKeepShared, true>), grid, block, lds, stream, p);
+            else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxKeepShared, false>), grid, block, lds, stream, p);
+            return hipGetLastError();
+        }
+    }
     if (p.binomial) {
         if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, true>), grid, block, lds, stream, p);
         else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, true>), grid, block, lds, stream, p);

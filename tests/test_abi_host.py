@@ -82,12 +82,17 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     # beyond one tile per CU: many tiles of 4 wavefronts x 4 rows (12 result rows); cached loads for large float32
     mid, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4256)
     assert (mid["schedule"], mid["rows"], mid["waves_per_block"]) == (2, 4, 4) and blocks == 18 * 236
-    assert mid["flags"] == pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES
+    # between half the last-level cache and about 400 MB: non-temporal loads, but the rows two tiles share stay in L2
+    assert mid["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_ALIGNED_STORES
     big, blocks = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920)
-    assert (big["rows"], big["waves_per_block"]) == (4, 4) and big["flags"] & pkg.HARRIS_TUNE_CACHED_LOADS and blocks == 64 * 90 * 8
+    assert (big["rows"], big["waves_per_block"]) == (4, 4) and blocks == 64 * 90 * 8
+    assert big["flags"] == pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES
+    # lanes narrower than 16 bytes have no mixed policy: default-policy loads from 128 MB on
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4258)[0]["flags"] == pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES
     # 8-bit input: non-temporal loads; 35 strips of at most 240 columns cover 8188
     u8, blocks = pkg.harris_plan(pkg.HARRIS_U8, 1, 8192, 8192)
-    assert u8["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES and blocks == 35 * 683
+    assert u8["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_ALIGNED_STORES and blocks == 35 * 683
+    assert pkg.harris_plan(pkg.HARRIS_U8, 1, 64, 98, rgb_align=1)[0]["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES
     # narrower lanes and bands never move strip borders
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 98)[0]["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 96, tuning=dict(schedule=1))[0]["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES
@@ -112,7 +117,7 @@ def test_plan_rejects_bad_arguments(pkg):
         with pytest.raises(E) as e:
             pkg.harris_plan(*args)
         assert e.value.status == status
-    for bad in (dict(px=3), dict(px=4, prefetch=5), dict(schedule=1, px=4, waves_per_block=3), dict(waves_per_block=1), dict(flags=64), dict(flags=12), dict(flags=48), dict(schedule=1, flags=16), dict(px=2, flags=16), dict(rows=-1),
+    for bad in (dict(px=3), dict(px=4, prefetch=5), dict(schedule=1, px=4, waves_per_block=3), dict(waves_per_block=1), dict(flags=128), dict(flags=12), dict(flags=48), dict(flags=64), dict(flags=64 | 4), dict(schedule=1, flags=64 | 8), dict(px=2, flags=64 | 8), dict(schedule=1, flags=16), dict(px=2, flags=16), dict(rows=-1),
                 dict(schedule=3), dict(schedule=2, rows=7), dict(schedule=2, px=2, rows=5), dict(schedule=2, waves_per_block=1), dict(schedule=2, waves_per_block=17),
                 dict(schedule=2, prefetch=3), dict(schedule=2, px=8)):
         with pytest.raises(E) as e:

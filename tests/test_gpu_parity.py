@@ -147,6 +147,22 @@ def test_tile_schedule_other_heights(gpu, oracle, rows):
     check(run_gpu(gpu, u8, k=K, window=1, tuning=dict(schedule=2, px=4, rows=rows, waves_per_block=3)), oracle.harris(u8, K, 1.0, 1))
 
 
+@pytest.mark.parametrize("rows", [4, 5, 6, 8, 9, 10])
+def test_tile_schedule_shared_rows_kept_in_cache(gpu, oracle, rows):
+    # Non-temporal loads except for the rows two tiles share: its own kernel instances (float32
+    # and 8-bit, both windows), including tiles of two wavefronts, where the first and the last
+    # wavefront are neighbours, and tile heights below 8, where the two groups of rows overlap.
+    H, W = 97, 4 * 131
+    flags = gpu.HARRIS_TUNE_STREAM_LOADS | gpu.HARRIS_TUNE_KEEP_SHARED_ROWS
+    for rgb in (hi.white_noise_f32(23, 2, H, W), hi.white_noise_u8(24, 2, H, W)):
+        for window in (0, 1):
+            want = oracle.harris(rgb, K, 1.0, window)
+            for waves in (2, 3, 5):
+                tune = dict(schedule=2, px=4, rows=rows, waves_per_block=waves, flags=flags)
+                say("case tiles keep-shared %s window=%d %s" % (rgb.dtype, window, tune))
+                check(run_gpu(gpu, rgb, k=K, window=window, tuning=tune), want)
+
+
 def test_tile_schedule_shapes(gpu, oracle):
     for H, W in SHAPES:
         rgb = hi.white_noise_f32(200 + H + W, 2, H, W)
