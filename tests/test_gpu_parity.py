@@ -405,6 +405,23 @@ def test_full_size_single_images(gpu, oracle, name):
     say("   ratio to bound: %.3g" % check(got, want))
 
 
+@pytest.mark.parametrize("name", ["noise_f32_1536x2560", "blobs_f32_2832x4256"])
+def test_full_size_psnr_of_the_thesis_operator(gpu, oracle, name):
+    # The thesis's own consistency check (section 4.4): mean squared error and PSNR against a
+    # reference output, "always above 170 dB", on its two image sizes, for the operator exactly
+    # as its listings define it (Sobel matrices scaled by 1/12).  The reference here is the
+    # float64 oracle; the peak is taken as 1, the range of the input image (the thesis does not
+    # say which peak it uses).
+    rgb = hi.make(name)
+    say("case psnr %s" % name)
+    got = run_gpu(gpu, rgb, k=K, sobel_scale=S12).astype(np.float64)
+    want = oracle.harris(rgb, K, S12, precision="f64", nthreads=oracle.hardware_threads())
+    mse = float(np.mean((got - want) ** 2))
+    psnr = 10.0 * np.log10(1.0 / mse) if mse > 0 else float("inf")
+    say("   mse %.3g  psnr %.1f dB" % (mse, psnr))
+    assert psnr > 170.0
+
+
 def test_full_size_batch_of_64(gpu, oracle):
     import torch
     name = "rects_f32_64x1080x1920"
