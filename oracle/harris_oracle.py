@@ -56,6 +56,9 @@ def _load():
             getattr(lib, "harris_ref_coarsity_" + sfx).argtypes = [p, p, p, ci, ci, real, p]
             for stage in ("gray", "conv3x3", "sobel", "mul", "sum3x3", "coarsity"):
                 getattr(lib, "harris_ref_%s_%s" % (stage, sfx)).restype = None
+        for name in ("harris_ref_round_binary16", "harris_ref_round_bfloat16"):
+            getattr(lib, name).argtypes = [_f32p, ctypes.c_longlong, ctypes.POINTER(ctypes.c_uint16)]
+            getattr(lib, name).restype = None
         lib.harris_ref_hardware_threads.restype = ci
         _lib = lib
     return _lib
@@ -155,4 +158,14 @@ def coarsity(sxx: np.ndarray, sxy: np.ndarray, syy: np.ndarray, k: float) -> np.
     out = np.empty_like(sxx)
     getattr(_load(), "harris_ref_coarsity_" + _sfx(sxx.dtype))(_ptr(sxx), _ptr(sxy), _ptr(syy),
                                                               sxx.shape[0], sxx.shape[1], k, _ptr(out))
+    return out
+
+
+def round_to_16bit(values: np.ndarray, fmt: str) -> np.ndarray:
+    """float32 array -> bit patterns (uint16, same shape) of the nearest binary16 ("f16") or
+    bfloat16 ("bf16") values: round to nearest, ties to even, overflow to infinity."""
+    a = np.ascontiguousarray(values, dtype=np.float32)
+    out = np.empty(a.shape, dtype=np.uint16)
+    fn = {"f16": "harris_ref_round_binary16", "bf16": "harris_ref_round_bfloat16"}[fmt]
+    getattr(_load(), fn)(_ptr(a), a.size, out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)))
     return out

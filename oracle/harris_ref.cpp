@@ -280,6 +280,45 @@ void harris_ref_coarsity_f64(const double* sxx, const double* sxy, const double*
     coarsity<double>(sxx, sxy, syy, H, W, kappa, out, 1);
 }
 
+// Rounding of a finished float32 result to a 16-bit storage format, for the library's
+// reduced-precision result options (not part of the thesis, whose arrays are all f32; the
+// definition is IEEE 754 round-to-nearest, ties to even, overflow to infinity).  Written from
+// that definition in double arithmetic: find the binade, divide by the spacing of the target
+// format there, round to an integer with the default rounding mode, rebuild the bit pattern.
+//   binary16: 11 significant bits, exponents -14..15, subnormals spaced 2^-24.
+//   bfloat16:  8 significant bits, exponents -126..127, subnormals spaced 2^-133.
+static uint16_t round_to_16bit(float x, int significant_bits, int min_exponent, int exponent_bits) {
+    const int bias = (1 << (exponent_bits - 1)) - 1;
+    const int fraction_bits = significant_bits - 1;
+    const uint16_t sign = std::signbit(x) ? (uint16_t)0x8000 : (uint16_t)0;
+    const uint16_t all_ones_exponent = (uint16_t)(((1 << exponent_bits) - 1) << fraction_bits);
+    if (std::isnan(x)) return (uint16_t)(sign | all_ones_exponent | (1 << (fraction_bits - 1)));   // quiet NaN
+    if (std::isinf(x)) return (uint16_t)(sign | all_ones_exponent);
+    const double a = std::fabs((double)x);
+    if (a == 0.0) return sign;
+    int e;
+    std::frexp(a, &e);                         // a = f * 2^e with f in [0.5, 1): floor(log2 a) = e - 1
+    int binade = e - 1;
+    if (binade < min_exponent) binade = min_exponent;                   // subnormal range: fixed spacing
+    const double spacing = std::ldexp(1.0, binade - fraction_bits);
+    const double rounded = std::nearbyint(a / spacing) * spacing;        // ties to even (default rounding mode)
+    if (rounded >= std::ldexp(1.0, bias + 1)) return (uint16_t)(sign | all_ones_exponent);   // past the largest finite value
+    if (rounded < std::ldexp(1.0, min_exponent))                        // zero or subnormal: the fraction counts spacings
+        return (uint16_t)(sign | (uint16_t)std::lround(rounded / std::ldexp(1.0, min_exponent - fraction_bits)));
+    std::frexp(rounded, &e);
+    const int exponent = e - 1;
+    const double fraction = rounded / std::ldexp(1.0, exponent) - 1.0;  // in [0, 1), a multiple of 2^-fraction_bits
+    return (uint16_t)(sign | (uint16_t)((exponent + bias) << fraction_bits) | (uint16_t)std::lround(std::ldexp(fraction, fraction_bits)));
+}
+
+void harris_ref_round_binary16(const float* in, long long count, uint16_t* out) {
+    for (long long i = 0; i < count; ++i) out[i] = round_to_16bit(in[i], 11, -14, 5);
+}
+
+void harris_ref_round_bfloat16(const float* in, long long count, uint16_t* out) {
+    for (long long i = 0; i < count; ++i) out[i] = round_to_16bit(in[i], 8, -126, 8);
+}
+
 int harris_ref_hardware_threads(void) { return (int)std::max(1u, std::thread::hardware_concurrency()); }
 
 }  // extern "C"

@@ -350,6 +350,44 @@ def test_batch_and_threads_do_not_change_results(oracle):
     assert np.array_equal(oracle.harris(rgb, KF, precision="f64", nthreads=4), oracle.harris(rgb, KF, precision="f64"))
 
 
+# ---------------------------------------------------------------- rounding to 16-bit results
+
+def test_rounding_to_binary16_and_bfloat16(oracle):
+    # The oracle's rounding (written from the IEEE definition in double arithmetic) against two
+    # library conversions that share nothing with it: numpy's float32 -> float16 and torch's
+    # float32 -> bfloat16, both round-to-nearest-even.
+    import torch
+    f16 = lambda a: oracle.round_to_16bit(a, "f16")
+    bf16 = lambda a: oracle.round_to_16bit(a, "bf16")
+    rng = np.random.default_rng(7)
+    x = rng.integers(0, 2 ** 32, size=1 << 20, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    x = x[~np.isnan(x)]                                       # every binade, both signs, subnormals, infinities
+    with np.errstate(over="ignore"):
+        assert np.array_equal(f16(x), x.astype(np.float16).view(np.uint16))
+    assert np.array_equal(bf16(x), torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+    # every tie of binary16: the midpoint of two neighbouring values goes to the one with an even fraction
+    h = np.arange(0, 0x7c00, dtype=np.uint16)                 # all finite non-negative binary16 values
+    lo = h[:-1].view(np.float16).astype(np.float64); hi_ = h[1:].view(np.float16).astype(np.float64)
+    mid = ((lo + hi_) / 2).astype(np.float32)                 # exact in float32
+    assert np.array_equal(mid.astype(np.float64), (lo + hi_) / 2)
+    want = np.where(h[:-1] % 2 == 0, h[:-1], h[1:])
+    assert np.array_equal(f16(mid), want) and np.array_equal(f16(-mid), want | 0x8000)
+    # hand-picked values
+    cases16 = [(1.0, 0x3c00), (-2.0, 0xc000), (65504.0, 0x7bff), (65519.996, 0x7bff), (65520.0, 0x7c00), (1e9, 0x7c00),
+               (2.0 ** -24, 0x0001), (2.0 ** -25, 0x0000), (2.0 ** -25 * 1.0000002, 0x0001), (2.0 ** -14, 0x0400),
+               (0.0, 0x0000), (-0.0, 0x8000), (float("inf"), 0x7c00), (float("-inf"), 0xfc00), (1.0 + 2.0 ** -11, 0x3c00),
+               (1.0 + 3 * 2.0 ** -11, 0x3c02)]
+    for v, bits in cases16:
+        assert int(f16(np.array([v], dtype=np.float32))[0]) == bits, (v, hex(bits))
+    cases_b = [(1.0, 0x3f80), (1.0 + 2.0 ** -8, 0x3f80), (1.0 + 3 * 2.0 ** -8, 0x3f82), (-1.5, 0xbfc0), (3.3895314e38, 0x7f7f),
+               (3.4e38, 0x7f80), (0.0, 0x0000), (-0.0, 0x8000), (float("inf"), 0x7f80), (2.0 ** -133, 0x0001), (2.0 ** -134, 0x0000)]
+    for v, bits in cases_b:
+        assert int(bf16(np.array([v], dtype=np.float32))[0]) == bits, (v, hex(bits))
+    nan = np.array([np.nan], dtype=np.float32)
+    assert (int(f16(nan)[0]) & 0x7c00) == 0x7c00 and (int(f16(nan)[0]) & 0x03ff) != 0
+    assert (int(bf16(nan)[0]) & 0x7f80) == 0x7f80 and (int(bf16(nan)[0]) & 0x007f) != 0
+
+
 # ---------------------------------------------------------------- input generators (host logic)
 
 def test_generators_are_deterministic_and_in_range():
