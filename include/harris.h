@@ -45,7 +45,8 @@ typedef enum harris_status {
     HARRIS_ERR_NULL = -1,    /* rgb or out is NULL although the result is not empty        */
     HARRIS_ERR_SHAPE = -2,   /* batch < 0, H < 4, W < 4, W > 2^28, more than 2^31-1 tiles, or
                                 pitches smaller than the image                               */
-    HARRIS_ERR_ARG = -3,     /* k or sobel_scale not finite, unknown dtype/window/tuning    */
+    HARRIS_ERR_ARG = -3,     /* k or sobel_scale not finite, unknown dtype/window/tuning,
+                                misaligned pointer                                          */
     HARRIS_ERR_LAUNCH = -4   /* the HIP runtime refused the kernel launch                   */
 } harris_status;
 
@@ -165,6 +166,30 @@ int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W,
                             float k, float sobel_scale, int window, float* out,
                             const harris_tuning* tuning, void* stream);
 
+/* Element type of the result. */
+typedef enum harris_out_dtype {
+    HARRIS_OUT_F32 = 0,      /* float32, as the thesis's pipeline produces it                     */
+    HARRIS_OUT_F16 = 1,      /* IEEE binary16                                                     */
+    HARRIS_OUT_BF16 = 2      /* bfloat16                                                          */
+} harris_out_dtype;
+
+/*
+ * harris_coarsity_pitched with a choice of result type, to cut the 4 bytes per pixel that the
+ * float32 result costs (the thesis's arrays are all float32, section 4.2; this is an extension).
+ * The coarsity is computed in float32 exactly as by the other entry points and rounded to the
+ * result type when it is stored: to nearest, ties to even, values beyond the largest finite
+ * number to infinity (binary16 overflows from 65520 on: with sobel_scale 1 and inputs in [0, 1]
+ * results stay below that; larger inputs may not).
+ *   out        device, element type given by out_dtype (a harris_out_dtype), [batch][H-4][W-4]
+ *              with the pitches of `layout` counted in result elements; fully overwritten
+ *   tuning     as in harris_coarsity_ex, but 16-bit results exist only in HARRIS_SCHEDULE_TILES
+ *              (else HARRIS_ERR_ARG); with aligned stores their strips are at most 224 columns
+ * The fastest path needs 8-byte aligned 16-bit result rows (pointer and pitches), W % 4 == 0.
+ */
+int harris_coarsity_typed(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
+                          float k, float sobel_scale, int window, void* out, int out_dtype,
+                          const harris_tuning* tuning, void* stream);
+
 /*
  * The launch shape harris_coarsity_ex would use for this problem (after applying
  * `tuning`, which may be NULL), written to *chosen; also the number of workgroups
@@ -174,6 +199,10 @@ int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W,
  */
 int harris_plan(int dtype, int batch, int H, int W, int rgb_align, int out_align,
                 const harris_tuning* tuning, harris_tuning* chosen, long long* n_blocks);
+
+/* The same for harris_coarsity_typed: out_dtype is a harris_out_dtype. */
+int harris_plan_typed(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int out_align,
+                      const harris_tuning* tuning, harris_tuning* chosen, long long* n_blocks);
 
 /*
  * The same result computed by several kernels that keep their intermediate images in

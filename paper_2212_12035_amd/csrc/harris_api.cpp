@@ -9,28 +9,30 @@
 
 namespace {
 
-constexpr int kVersion = 200;   // 0.2.0
+constexpr int kVersion = 300;   // 0.3.0
 
 bool power_of_two_aligned(uintptr_t p, unsigned bytes) { return (p & (uintptr_t)(bytes - 1)) == 0; }
 
 int elem_size(int dtype) { return dtype == HARRIS_U8 ? 1 : 4; }
+int out_elem_size(int out_dtype) { return out_dtype == HARRIS_OUT_F32 ? 4 : 2; }
 
 // Can every lane load px input elements and store its result columns with single
-// vector accesses?  Loads are px*elem bytes wide up to 16; stores are min(px,4) floats.
-bool px_fits(int px, int dtype, int W, int rgb_align, int out_align) {
+// vector accesses?  Loads are px*elem bytes wide up to 16; stores are min(px,4) result elements.
+bool px_fits(int px, int dtype, int out_dtype, int W, int rgb_align, int out_align) {
     if (px < 1 || W % px != 0) return false;
     int load_bytes = px * elem_size(dtype);
     if (load_bytes > 16) load_bytes = 16;
-    int store_bytes = (px < 4 ? px : 4) * 4;
+    int store_bytes = (px < 4 ? px : 4) * out_elem_size(out_dtype);
     return rgb_align % load_bytes == 0 && out_align % store_bytes == 0;
 }
 
-int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const harris_tuning* tuning,
+int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int out_align, const harris_tuning* tuning,
          harris_tuning* chosen, long long* n_blocks, harris_launch::Params* params) {
     if (dtype != HARRIS_F32 && dtype != HARRIS_U8) return HARRIS_ERR_ARG;
+    if (out_dtype != HARRIS_OUT_F32 && out_dtype != HARRIS_OUT_F16 && out_dtype != HARRIS_OUT_BF16) return HARRIS_ERR_ARG;
     if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
     if (W > (1 << 28)) return HARRIS_ERR_SHAPE;      // byte offsets within a row are 32-bit
-    if (rgb_align < 1 || out_align < 4) return HARRIS_ERR_ARG;
+    if (rgb_align < 1 || out_align < out_elem_size(out_dtype)) return HARRIS_ERR_ARG;
     harris_tuning t = {0, 0, 0, 0, 0, 0u};
     if (tuning) t = *tuning;
     if (t.flags & ~(HARRIS_TUNE_NO_ALTERNATE | HARRIS_TUNE_NO_XCD_REMAP | HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS |
@@ -44,13 +46,14 @@ int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const
     if (t.px == 0) {
         t.px = 1;
         for (int px = 4; px >= 2; px /= 2)
-            if (px_fits(px, dtype, W, rgb_align, out_align)) { t.px = px; break; }
-    } else if (!((t.px == 1 || t.px == 2 || t.px == 4 || t.px == 8) && px_fits(t.px, dtype, W, rgb_align, out_align))) {
+            if (px_fits(px, dtype, out_dtype, W, rgb_align, out_align)) { t.px = px; break; }
+    } else if (!((t.px == 1 || t.px == 2 || t.px == 4 || t.px == 8) && px_fits(t.px, dtype, out_dtype, W, rgb_align, out_align))) {
         return HARRIS_ERR_ARG;
     }
     if (t.rows < 0 || t.prefetch < 0 || t.waves_per_block < 0) return HARRIS_ERR_ARG;
     // px = 8 and a prefetch depth exist only in the band schedule.
     if (t.schedule == 0) t.schedule = t.px <= 4 && t.prefetch == 0 ? HARRIS_SCHEDULE_TILES : HARRIS_SCHEDULE_BANDS;
+    if (out_dtype != HARRIS_OUT_F32 && t.schedule != HARRIS_SCHEDULE_TILES) return HARRIS_ERR_ARG;   // 16-bit results: tile kernel only
     // Strip borders on 64-byte boundaries of the result rows: the tile kernel with 16-byte lanes.
     const bool can_align = t.schedule == HARRIS_SCHEDULE_TILES && t.px == 4;
     if ((t.flags & (HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_KEEP_SHARED_ROWS)) && !can_align) return HARRIS_ERR_ARG;
@@ -60,8 +63,10 @@ int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const
     if (!(t.flags & (HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_PLAIN_STORES)))
         t.flags |= can_align ? HARRIS_TUNE_ALIGNED_STORES : HARRIS_TUNE_PLAIN_STORES;
     // As few strips as 64-lane wavefronts allow, all of the same width.  A moved border lies up
-    // to 12 columns right of the strip's nominal end, and the wavefront must reach that far.
-    const long long max_pitch = (long long)harris_launch::valid_lanes(t.px) * t.px - ((t.flags & HARRIS_TUNE_ALIGNED_STORES) ? 12 : 0);
+    // to one 64-byte block less a lane (12 float32 or 28 16-bit columns) right of the strip's
+    // nominal end, and the wavefront must reach that far.
+    const long long border_reach = (t.flags & HARRIS_TUNE_ALIGNED_STORES) ? 64 / out_elem_size(out_dtype) - 4 : 0;
+    const long long max_pitch = (long long)harris_launch::valid_lanes(t.px) * t.px - border_reach;
     const long long n_strips = m > 0 ? (m + max_pitch - 1) / max_pitch : 0;
     const long long pitch = n_strips > 0 ? ((m + n_strips - 1) / n_strips + t.px - 1) / t.px * t.px : max_pitch;
 
@@ -74,7 +79,7 @@ int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const
     // non-temporal with the shared rows kept at every size (8192x8192: 91.1 us against 91.8 us
     // non-temporal and 105 us default; 64x1080x1920: 176 / 181 / 176 us).
     const long long elem = elem_size(dtype);
-    const long long footprint = (long long)batch * (3LL * H * W * elem + 4LL * n * m);
+    const long long footprint = (long long)batch * (3LL * H * W * elem + (long long)out_elem_size(out_dtype) * n * m);
     if (!(t.flags & (HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS))) {
         if (dtype == HARRIS_F32 && footprint > (400LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
         else if (dtype == HARRIS_F32 && footprint > (128LL << 20) && can_align) t.flags |= HARRIS_TUNE_STREAM_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS;
@@ -165,6 +170,7 @@ int plan(int dtype, int batch, int H, int W, int rgb_align, int out_align, const
         params->n_blocks = (unsigned)blocks;
         params->waves_per_block = (unsigned)t.waves_per_block;
         params->flags = t.flags;
+        params->out_kind = (unsigned)out_dtype;
     }
     return HARRIS_OK;
 }
@@ -182,13 +188,19 @@ extern "C" {
 
 int harris_plan(int dtype, int batch, int H, int W, int rgb_align, int out_align,
                 const harris_tuning* tuning, harris_tuning* chosen, long long* n_blocks) {
-    return plan(dtype, batch, H, W, rgb_align, out_align, tuning, chosen, n_blocks, nullptr);
+    return plan(dtype, HARRIS_OUT_F32, batch, H, W, rgb_align, out_align, tuning, chosen, n_blocks, nullptr);
 }
 
-int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
-                            float k, float sobel_scale, int window, float* out,
-                            const harris_tuning* tuning, void* stream) {
+int harris_plan_typed(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int out_align,
+                      const harris_tuning* tuning, harris_tuning* chosen, long long* n_blocks) {
+    return plan(dtype, out_dtype, batch, H, W, rgb_align, out_align, tuning, chosen, n_blocks, nullptr);
+}
+
+int harris_coarsity_typed(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
+                          float k, float sobel_scale, int window, void* out, int out_dtype,
+                          const harris_tuning* tuning, void* stream) {
     if (dtype != HARRIS_F32 && dtype != HARRIS_U8) return HARRIS_ERR_ARG;
+    if (out_dtype != HARRIS_OUT_F32 && out_dtype != HARRIS_OUT_F16 && out_dtype != HARRIS_OUT_BF16) return HARRIS_ERR_ARG;
     if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
     if (!isfinite(k) || !isfinite(sobel_scale)) return HARRIS_ERR_ARG;
     if (window != HARRIS_WINDOW_BOX && window != HARRIS_WINDOW_BINOMIAL) return HARRIS_ERR_ARG;
@@ -206,7 +218,7 @@ int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W,
     if (lay.out_row_pitch < m || (n > 0 && lay.out_image_pitch < (n - 1) * lay.out_row_pitch + m)) return HARRIS_ERR_SHAPE;
     const bool empty = batch == 0 || H == 4 || W == 4;
     if (!empty && (rgb == nullptr || out == nullptr)) return HARRIS_ERR_NULL;
-    if (!empty && pointer_alignment(out) < 4) return HARRIS_ERR_ARG;
+    if (!empty && (int)pointer_alignment(out) < out_elem_size(out_dtype)) return HARRIS_ERR_ARG;
     if (!empty && dtype == HARRIS_F32 && pointer_alignment(rgb) < 4) return HARRIS_ERR_ARG;
 
     // Alignment that every row start shares: the base pointer's and each pitch's (in bytes).
@@ -224,14 +236,14 @@ int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W,
         rgb_align = common_alignment(rgb_align, lay.rgb_image_pitch * e);
         out_align = pointer_alignment(out);
         if (out_align > 16) out_align = 16;
-        out_align = common_alignment(out_align, lay.out_row_pitch * 4);
-        out_align = common_alignment(out_align, lay.out_image_pitch * 4);
+        out_align = common_alignment(out_align, lay.out_row_pitch * out_elem_size(out_dtype));
+        out_align = common_alignment(out_align, lay.out_image_pitch * out_elem_size(out_dtype));
     }
 
     harris_launch::Params p;
     harris_tuning shape;
     long long n_blocks = 0;
-    int rc = plan(dtype, batch, H, W, (int)rgb_align, (int)out_align, tuning, &shape, &n_blocks, &p);
+    int rc = plan(dtype, out_dtype, batch, H, W, (int)rgb_align, (int)out_align, tuning, &shape, &n_blocks, &p);
     if (rc != HARRIS_OK) return rc;
     if (empty) return HARRIS_OK;
 
@@ -248,6 +260,12 @@ int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W,
     p.k = k;
     p.binomial = window == HARRIS_WINDOW_BINOMIAL ? 1 : 0;
     return harris_launch::launch(p, shape, n_blocks, dtype, stream);
+}
+
+int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
+                            float k, float sobel_scale, int window, float* out,
+                            const harris_tuning* tuning, void* stream) {
+    return harris_coarsity_typed(rgb, dtype, batch, H, W, layout, k, sobel_scale, window, out, HARRIS_OUT_F32, tuning, stream);
 }
 
 int harris_coarsity_ex(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale,

@@ -152,6 +152,39 @@ __device__ __forceinline__ void store_row(const float (&o)[PX], __amdgpu_buffer_
     }
 }
 
+// float32 -> bit pattern of the nearest binary16 / bfloat16 value (ties to even, overflow to
+// infinity).  binary16 by the hardware conversion (round-to-nearest-even is the mode HIP
+// kernels run in); bfloat16 by adding half of the dropped part's range, plus the lowest kept
+// bit so that ties go to even, and truncating; NaN stays NaN.
+__device__ __forceinline__ uint32_t to_f16_bits(float x) {
+    return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)x);
+}
+__device__ __forceinline__ uint32_t to_bf16_bits(float x) {
+    const uint32_t u = __float_as_uint(x);
+    const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return (u & 0x7fffffffu) > 0x7f800000u ? ((u >> 16) | 0x40u) : rounded;
+}
+
+// PX results of one lane as 16-bit values (BF: bfloat16, else binary16); voff is the lane's
+// byte offset in the row (2 bytes per column).
+template <int PX, bool BF>
+__device__ __forceinline__ void store_row_16(const float (&o)[PX], __amdgpu_buffer_rsrc_t rs, uint32_t voff) {
+    uint32_t h[PX];
+#pragma unroll
+    for (int i = 0; i < PX; ++i) h[i] = BF ? to_bf16_bits(o[i]) : to_f16_bits(o[i]);
+    if constexpr (PX >= 4) {
+#pragma unroll
+        for (int j = 0; j < PX / 4; ++j) {
+            u32x2 v = {h[4 * j] | (h[4 * j + 1] << 16), h[4 * j + 2] | (h[4 * j + 3] << 16)};
+            __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff + 8 * j, 0, HARRIS_STORE_AUX);
+        }
+    } else if constexpr (PX == 2) {
+        __builtin_amdgcn_raw_buffer_store_b32(h[0] | (h[1] << 16), rs, voff, 0, HARRIS_STORE_AUX);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)h[0], rs, voff, 0, HARRIS_STORE_AUX);
+    }
+}
+
 // Stage a0 + a1: element i of plane c as float (8-bit values are converted; their
 // 1/255 is folded into the gray weights), then gray = wr*R + wg*G + wb*B.
 template <typename In, int PX>
@@ -300,7 +333,7 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
 
     const size_t plane = (size_t)p.in_plane_pitch;
     const In* img_in = static_cast<const In*>(p.rgb) + (size_t)img * (size_t)p.in_image_pitch;
-    float* img_out = p.out + (size_t)img * (size_t)p.out_image_pitch;
+    float* img_out = static_cast<float*>(p.out) + (size_t)img * (size_t)p.out_image_pitch;   // float32 results only
 
     // Input row read at step t.  Steps past the band's end (the loop runs in trips of U
     // steps, and the queue reads D rows ahead) get an empty descriptor: such a load
@@ -353,6 +386,15 @@ __global__ __launch_bounds__(256) void harris_fused_kernel(const harris_launch::
 }
 
 
+// Makes the compiler finish these values here: without it the last multiply-add of a result
+// is moved down to the stores, and its three operands stay in registers instead of the one
+// result (the tile kernel holds RW rows of results until its store burst).
+template <int PX>
+__device__ __forceinline__ void pin_values(float (&v)[PX]) {
+#pragma unroll
+    for (int i = 0; i < PX; ++i) asm volatile("" : "+v"(v[i]));
+}
+
 // ---------------------------------------------------------------- the tile kernel
 //
 // Second schedule, for images too small to keep long-lived wavefronts busy: a
@@ -393,19 +435,22 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 
     const unsigned col = (unsigned)strip * p.strip_pitch + lane * PX;
     const unsigned lcol = min(col, (unsigned)(p.W - PX));
+    // Results are float32 or 16-bit: esh is log2 of a result element's bytes.
+    const unsigned esh = p.out_kind == HARRIS_OUT_F32 ? 2u : 1u;
     // With aligned stores the border between this strip and the next lies, in each result row,
     // on the first 64-byte boundary of that row's address at or after the nominal border: up to
-    // 12 columns further right.  border_mask is 15 (columns per 64 bytes, minus one) or 0.
-    const unsigned border_mask = (p.flags & HARRIS_TUNE_ALIGNED_STORES) ? 15u : 0u;
+    // 12 (float32) or 28 (16-bit) columns further right.  border_mask is the number of columns
+    // per 64 bytes, minus one (15 or 31), or 0.
+    const unsigned border_mask = (p.flags & HARRIS_TUNE_ALIGNED_STORES) ? (64u >> esh) - 1u : 0u;
     const unsigned x0 = (unsigned)strip * p.strip_pitch;        // first result column of this strip
     // Lanes beyond the strip's columns, the border's reach and the 4-column halo request nothing
     // (out-of-range offset).
-    const uint32_t load_voff = lane * PX < p.strip_pitch + 4 + (border_mask & 12u) ? lcol * (uint32_t)sizeof(In) : 0x80000000u;
+    const uint32_t load_voff = lane * PX < p.strip_pitch + 4 + (border_mask & ~3u) ? lcol * (uint32_t)sizeof(In) : 0x80000000u;
     const uint32_t in_row_bytes = (uint32_t)p.W * (uint32_t)sizeof(In);
 
     const size_t plane = (size_t)p.in_plane_pitch;
     const In* img_in = static_cast<const In*>(p.rgb) + (size_t)img * (size_t)p.in_image_pitch;
-    float* img_out = p.out + (size_t)img * (size_t)p.out_image_pitch;
+    const uintptr_t img_out = reinterpret_cast<uintptr_t>(p.out) + (((size_t)img * (size_t)p.out_image_pitch) << esh);
 
     // All RW rows of this wavefront at once; rows below the image get an empty descriptor.
     RawRow<In, PX> raw[RW];
@@ -438,16 +483,16 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
     int sy = y_wave;
     asm volatile("" : "+s"(sx0), "+s"(sy) : : "memory");
     const unsigned sx1 = sx0 + p.strip_pitch;
-    const uintptr_t out_first = reinterpret_cast<uintptr_t>(img_out) + ((size_t)sy * (size_t)p.out_row_pitch) * 4u;
+    const uintptr_t out_first = img_out + (((size_t)sy * (size_t)p.out_row_pitch) << esh);
     static_for<0, RW>([&](auto jj) {
         constexpr int j = decltype(jj)::value;
-        const uintptr_t row_addr = out_first + (size_t)j * ((size_t)p.out_row_pitch * 4u);
-        const unsigned a = (unsigned)(row_addr >> 2);           // address in floats
+        const uintptr_t row_addr = out_first + (size_t)j * ((size_t)p.out_row_pitch << esh);
+        const unsigned a = (unsigned)(row_addr >> esh);         // address in result elements
         const unsigned b0 = sx0 == 0 ? 0u : sx0 + ((0u - (a + sx0)) & border_mask);
         const unsigned b1 = min((unsigned)p.m, sx1 + ((0u - (a + sx1)) & border_mask));
-        const uint32_t bytes = (j < out_rows && b1 > b0) ? (b1 - b0) * 4u : 0u;
-        out_rs[j] = make_rsrc(reinterpret_cast<const float*>(row_addr) + b0, bytes);
-        out_lead[j] = (sx0 - b0) * 4u;
+        const uint32_t bytes = (j < out_rows && b1 > b0) ? (b1 - b0) << esh : 0u;
+        out_rs[j] = make_rsrc(reinterpret_cast<const void*>(row_addr + ((size_t)b0 << esh)), bytes);
+        out_lead[j] = (sx0 - b0) << esh;
     });
     __builtin_amdgcn_sched_barrier(0);
 
@@ -466,8 +511,12 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 #pragma unroll
             for (int i = 0; i < PX; ++i) my_halo[(size_t)t * kWave * PX + i] = gc[i];
         }
-        if constexpr (t < 4) row_step<(t < 2 ? 0 : 1), t % 3, PX, BINOM>(lb, gc, p.k, none);
-        else row_step<2, t % 3, PX, BINOM>(lb, gc, p.k, results[t - 4]);
+        if constexpr (t < 4) {
+            row_step<(t < 2 ? 0 : 1), t % 3, PX, BINOM>(lb, gc, p.k, none);
+        } else {
+            row_step<2, t % 3, PX, BINOM>(lb, gc, p.k, results[t - 4]);
+            pin_values<PX>(results[t - 4]);
+        }
         // Each row is worked through as soon as it has arrived: without this the compiler
         // gathers the arithmetic of all rows behind the wait for the last one.
         __builtin_amdgcn_sched_barrier(0);
@@ -482,16 +531,29 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 #pragma unroll
             for (int i = 0; i < PX; ++i) gc[i] = below[(size_t)(t - RW) * kWave * PX + i];
             row_step<2, t % 3, PX, BINOM>(lb, gc, p.k, results[t - 4]);
+            pin_values<PX>(results[t - 4]);
         });
     }
 
     // The last wavefront skips the four rows it has no data for.
     __builtin_amdgcn_sched_barrier(0);
-    const uint32_t lane_bytes = lane * PX * 4u;
-    static_for<0, RW>([&](auto jj) {
-        constexpr int j = decltype(jj)::value;
-        if (j < RW - 4 || wave + 1 < n_waves) store_row<PX>(results[j], out_rs[j], lane_bytes + out_lead[j]);
-    });
+    const uint32_t lane_bytes = (lane * PX) << esh;
+    if (p.out_kind == HARRIS_OUT_F32) {
+        static_for<0, RW>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+            if (j < RW - 4 || wave + 1 < n_waves) store_row<PX>(results[j], out_rs[j], lane_bytes + out_lead[j]);
+        });
+    } else if (p.out_kind == HARRIS_OUT_F16) {
+        static_for<0, RW>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+            if (j < RW - 4 || wave + 1 < n_waves) store_row_16<PX, false>(results[j], out_rs[j], lane_bytes + out_lead[j]);
+        });
+    } else {
+        static_for<0, RW>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+            if (j < RW - 4 || wave + 1 < n_waves) store_row_16<PX, true>(results[j], out_rs[j], lane_bytes + out_lead[j]);
+        });
+    }
 }
 
 template <typename In, int PX, int D>
@@ -551,6 +613,7 @@ hipError_t launch_px(const harris_launch::Params& p, const harris_tuning& t, dim
             return hipErrorInvalidValue;
         }
     }
+    if (p.out_kind != HARRIS_OUT_F32) return hipErrorInvalidValue;      // the band kernel stores float32 only
     switch (t.prefetch) {
         case 2: return launch_bands<In, PX, 2>(p, grid, block, stream);
         case 3: return launch_bands<In, PX, 3>(p, grid, block, stream);

@@ -47,9 +47,9 @@ HARRIS_HOST_DEVICE inline unsigned fastdiv(unsigned x, const FastDiv& f) {
 // together, so that a few wide scalar loads fetch it at once.
 struct Params {
     const void* rgb;        // device, [batch][3][H][W] with the pitches below
-    float* out;             // device, [batch][n][m] with the pitches below
+    void* out;              // device, [batch][n][m] with the pitches below; element type given by out_kind
     long long in_row_pitch, in_plane_pitch, in_image_pitch;   // in input elements
-    long long out_row_pitch, out_image_pitch;                 // in floats
+    long long out_row_pitch, out_image_pitch;                 // in result elements
     int H, W;               // input rows, columns
     int n, m;               // result rows, columns (H-4, W-4)
     int rows_per_band;      // result rows per band (BANDS) or per tile (TILES)
@@ -62,6 +62,7 @@ struct Params {
     float wr, wg, wb;       // gray weights, times the Sobel scale (and 1/255 for 8-bit input)
     float k;                // coarsity constant
     unsigned flags;         // HARRIS_TUNE_* bits
+    unsigned out_kind;      // a harris_out_dtype (16-bit results: tile kernel only)
     int binomial;           // 1: window [1 2 1; 2 4 2; 1 2 1], 0: unweighted 3x3 sum
     unsigned n_bands;       // bands (BANDS) or tiles down the image (TILES)
     unsigned blocks_x;      // BANDS: workgroups across a row of bands

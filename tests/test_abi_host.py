@@ -127,6 +127,28 @@ def test_plan_rejects_bad_arguments(pkg):
         pkg.harris_plan(0, 1, 64, 98, tuning=dict(px=4))
 
 
+def test_plan_for_16_bit_results(pkg):
+    # 16-bit results: tile kernel only; moved strip borders reach up to 28 columns (64 bytes),
+    # so strips are at most 224 columns; the widest lanes need 8-byte aligned result rows.
+    F16, BF16 = pkg.HARRIS_OUT_F16, pkg.HARRIS_OUT_BF16
+    shape, blocks = pkg.harris_plan_typed(pkg.HARRIS_F32, F16, 1, 1536, 2560)
+    assert shape["schedule"] == pkg.HARRIS_SCHEDULE_TILES and shape["px"] == 4 and shape["flags"] & pkg.HARRIS_TUNE_ALIGNED_STORES
+    assert blocks % 12 == 0                                     # ceil(2556 / 224) = 12 strips (11 for float32 results)
+    assert pkg.harris_plan_typed(pkg.HARRIS_F32, BF16, 1, 64, 96, out_align=4)[0]["px"] == 2
+    assert pkg.harris_plan_typed(pkg.HARRIS_F32, BF16, 1, 64, 96, out_align=2)[0]["px"] == 1
+    assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_F32, 1, 1536, 2560) == pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
+    for bad in (dict(out_dtype=3), dict(out_dtype=F16, tuning=dict(schedule=1)), dict(out_dtype=F16, tuning=dict(prefetch=3)),
+                dict(out_dtype=F16, out_align=1), dict(out_dtype=F16, tuning=dict(px=8))):
+        with pytest.raises(pkg.HarrisError) as e:
+            pkg.harris_plan_typed(pkg.HARRIS_F32, bad["out_dtype"], 1, 64, 96, out_align=bad.get("out_align", 16), tuning=bad.get("tuning"))
+        assert e.value.status == -3
+    lib = pkg.load_library()
+    one = ctypes.c_void_p(4096)
+    assert lib.harris_coarsity_typed(one, 0, 1, 64, 64, None, 0.04, 1.0, 0, one, 7, None, None) == -3
+    assert lib.harris_coarsity_typed(one, 0, 1, 64, 64, None, 0.04, 1.0, 0, ctypes.c_void_p(4097), 1, None, None) == -3
+    assert lib.harris_coarsity_typed(None, 0, 0, 64, 64, None, 0.04, 1.0, 0, None, 2, None, None) == 0
+
+
 def test_index_division_by_multiplication_is_exact(tmp_path):
     # The tile kernel splits its workgroup index with a multiply-high division whose constants
     # the host computes; the same header functions are checked here against the hardware division.

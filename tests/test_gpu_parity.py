@@ -322,6 +322,92 @@ def test_padded_rows_and_separate_planes(gpu, oracle):
     check(res.cpu().numpy(), oracle.harris(f32, K))
 
 
+# ---------------------------------------------------------------- 16-bit results
+
+def _as_f32(bits, fmt):
+    if fmt == "f16":
+        return bits.view(np.float16).astype(np.float32)
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def _ulp16(x, fmt):
+    # spacing of the 16-bit format at |x| (11 or 8 significant bits), at least the subnormal spacing
+    frac_bits, min_exp = (10, -14) if fmt == "f16" else (7, -126)
+    e = np.floor(np.log2(np.maximum(np.abs(x).astype(np.float64), 2.0 ** min_exp)))
+    return 2.0 ** (e - frac_bits)
+
+
+@pytest.mark.parametrize("fmt", ["f16", "bf16"])
+def test_16_bit_results(gpu, oracle, fmt):
+    # Two checks.  (1) The 16-bit result is the float32 result of the same kernel rounded to
+    # nearest-even, bit for bit (the rounding is the oracle's, applied to the GPU's own float32
+    # output: the same launch shape gives the same float32 values).  (2) Against the oracle's
+    # float32 result rounded the same way: the float32 bar plus one spacing of the 16-bit
+    # format (two float32 values within the bar may fall on either side of a rounding border).
+    import torch
+    tdt = torch.float16 if fmt == "f16" else torch.bfloat16
+    for rgb, scale in ((hi.rectangles_f32(71, 2, 61, 520), 1.0), (hi.white_noise_u8(72, 1, 45, 264), 1.0),
+                       (hi.white_noise_f32(73, 1, 37, 98), S12), (hi.white_noise_f32(74, 2, 22, 131), 1.0)):
+        B, _, H, W = rgb.shape
+        want32 = oracle.harris(rgb, K, scale)
+        want16 = _as_f32(oracle.round_to_16bit(want32, fmt), fmt)
+        src = torch.from_numpy(rgb).cuda()
+        for tune in (None, dict(schedule=2, rows=8, waves_per_block=3), dict(schedule=2, rows=5 if W % 4 == 0 else 4, waves_per_block=2, flags=gpu.HARRIS_TUNE_PLAIN_STORES)):
+            say("case %s result %s %s tuning %s" % (fmt, rgb.dtype, rgb.shape, tune))
+            out16 = torch.full((B, H - 4, W - 4), float("nan"), dtype=tdt, device="cuda")
+            gpu.harris_coarsity_typed(src, out16, K, scale, tuning=tune)
+            out32 = torch.empty((B, H - 4, W - 4), dtype=torch.float32, device="cuda")
+            gpu.harris_coarsity_typed(src, out32, K, scale, tuning=tune)
+            torch.cuda.synchronize()
+            bits = out16.view(torch.int16).cpu().numpy().view(np.uint16)
+            got32 = out32.cpu().numpy()
+            check(got32, want32)
+            assert np.array_equal(bits, oracle.round_to_16bit(got32, fmt))
+            got16 = _as_f32(bits, fmt)
+            bound = 1e-4 * float(np.abs(want32).max()) + 1e-6
+            assert np.all(np.abs(got16.astype(np.float64) - want16) <= bound + _ulp16(want32, fmt))
+
+
+def test_16_bit_results_layouts_and_overflow(gpu, oracle):
+    import torch
+    # every 8-byte phase of the result address with moved strip borders (64 bytes = 32 columns),
+    # dense and padded rows, several strips, guard bands
+    H, W = 23, 1000
+    n, m = H - 4, W - 4
+    rgb = hi.white_noise_f32(75, 2, H, W)
+    src = torch.from_numpy(rgb).cuda()
+    want = oracle.round_to_16bit(oracle.harris(rgb, K), "f16")
+    for pitch in (m, m + 4, m + 20):
+        for off in (0, 4, 12, 28):
+            flat = torch.full((2 * n * pitch + 128,), float("nan"), dtype=torch.float16, device="cuda")
+            view = flat[32 + off:32 + off + 2 * n * pitch].view(2, n, pitch)[:, :, :m]
+            say("case f16 borders pitch=%d offset=%d" % (pitch, off))
+            gpu.harris_coarsity_typed(src, view, K, tuning=dict(flags=gpu.HARRIS_TUNE_ALIGNED_STORES))
+            torch.cuda.synchronize()
+            got = view.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+            diff = np.abs(_as_f32(got, "f16").astype(np.float64) - _as_f32(want, "f16"))
+            assert np.all(diff <= 1e-4 * float(_as_f32(want, "f16").max()) + 1e-6 + _ulp16(_as_f32(want, "f16"), "f16"))
+            rest = flat.clone()
+            rest[32 + off:32 + off + 2 * n * pitch].view(2, n, pitch)[:, :, :m] = float("nan")
+            assert bool(torch.isnan(rest).all())
+    # binary16 overflows to infinity from 65520 on: an image scaled by 8 gives results 4096 times larger
+    big = (hi.rectangles_f32(76, 1, 40, 260) * 8.0).astype(np.float32)
+    want32 = oracle.harris(big, K)
+    assert np.abs(want32).max() > 65520
+    out = torch.empty((1, 36, 256), dtype=torch.float16, device="cuda")
+    gpu.harris_coarsity_typed(torch.from_numpy(big).cuda(), out, K)
+    torch.cuda.synchronize()
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    wantb = oracle.round_to_16bit(want32, "f16")
+    clear = np.abs(np.abs(want32) - 65520) > 1e-4 * np.abs(want32).max()       # away from the overflow border
+    assert np.array_equal(np.isinf(_as_f32(got, "f16"))[clear], np.isinf(_as_f32(wantb, "f16"))[clear])
+    assert np.isinf(_as_f32(got, "f16")).any()
+    # the band schedule has no 16-bit results
+    with pytest.raises(gpu.HarrisError) as e:
+        gpu.harris_coarsity_typed(torch.from_numpy(big).cuda(), out, K, tuning=dict(schedule=1))
+    assert e.value.status == -3
+
+
 # ---------------------------------------------------------------- unfused kernel groupings (baselines)
 
 @pytest.mark.parametrize("grouping", [1, 2, 3, 4])
