@@ -64,6 +64,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-groupings", action="store_true", help="skip timing the unfused kernel groupings")
     ap.add_argument("--warm-cache", action="store_true", help="reuse one buffer pair (cache-resident; not the roofline number)")
+    ap.add_argument("--out-dtype", choices=("f32", "f16", "bf16"), default="f32",
+                    help="type the result is stored in (the arithmetic stays float32); not the headline configuration")
     return ap.parse_args()
 
 
@@ -89,7 +91,9 @@ def main():
     host = harris_inputs.make(args.workload)
     n, m = H - 4, W - 4
     in_bytes = B * 3 * H * W * (1 if is_u8 else 4)
-    out_bytes = B * n * m * 4
+    out_torch = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.out_dtype]
+    out_code = {"f32": pkg.HARRIS_OUT_F32, "f16": pkg.HARRIS_OUT_F16, "bf16": pkg.HARRIS_OUT_BF16}[args.out_dtype]
+    out_bytes = B * n * m * (4 if args.out_dtype == "f32" else 2)
     algo_bytes = in_bytes + out_bytes                      # each input element read once, each result written once
     pixels = B * H * W
 
@@ -100,21 +104,21 @@ def main():
     n_pairs = max(1, min(n_pairs, int(0.8 * free_b // algo_bytes)))
     base = torch.from_numpy(host).to(dev)
     ins = [base] + [torch.roll(base, shifts=i, dims=2) for i in range(1, n_pairs)]
-    outs = [torch.empty((B, n, m), dtype=torch.float32, device=dev) for _ in range(n_pairs)]
+    outs = [torch.empty((B, n, m), dtype=out_torch, device=dev) for _ in range(n_pairs)]
 
     explicit_tuning = any((args.schedule, args.px, args.rows, args.prefetch, args.waves_per_block, args.flags))
     tuning = pkg.HarrisTuning(args.schedule, args.px, args.rows, args.prefetch, args.waves_per_block, args.flags)
-    shape, n_blocks = pkg.harris_plan(pkg.HARRIS_U8 if is_u8 else pkg.HARRIS_F32, B, H, W, tuning=tuning)
+    shape, n_blocks = pkg.harris_plan_typed(pkg.HARRIS_U8 if is_u8 else pkg.HARRIS_F32, out_code, B, H, W, tuning=tuning)
     stream = torch.cuda.current_stream(dev)
     sptr = ctypes.c_void_p(stream.cuda_stream)
     dtype_code = pkg.HARRIS_U8 if is_u8 else pkg.HARRIS_F32
     calls = [(ctypes.c_void_p(i.data_ptr()), ctypes.c_void_p(o.data_ptr())) for i, o in zip(ins, outs)]
     tref = ctypes.byref(tuning)
-    fn = lib.harris_coarsity_ex
+    fn = lib.harris_coarsity_typed
 
     def step(i):
         a, o = calls[i % n_pairs]
-        rc = fn(a, dtype_code, B, H, W, K_COARSITY, 1.0, 0, o, tref, sptr)
+        rc = fn(a, dtype_code, B, H, W, None, K_COARSITY, 1.0, 0, o, out_code, tref, sptr)
         if rc != 0:
             raise RuntimeError(pkg.harris_strerror(rc))
 
@@ -148,7 +152,7 @@ def main():
 
     # The thesis's kernel groupings (unfused baselines) on the same rotating buffers, for comparison.
     groupings = None
-    if not args.no_groupings:
+    if not args.no_groupings and args.out_dtype == "f32":
         groupings = {}
         ws_bytes = pkg.harris_grouped_workspace_bytes(1, B, H, W)
         ws = torch.empty(max(1, ws_bytes // 4), dtype=torch.float32, device=dev)
@@ -176,7 +180,7 @@ def main():
         torch.cuda.synchronize(dev)
 
     # Correctness of what was timed: pair 0 against the oracle (also the CPU baseline).
-    got = outs[0].cpu().numpy()
+    got = outs[0].float().cpu().numpy()
     cpu = None
     max_err = bound = None
     if not args.no_cpu_baseline:
@@ -195,6 +199,8 @@ def main():
         ta.sort(); to.sort()
         max_err = float(np.abs(got[:sample.shape[0]] - want).max())
         bound = 1e-4 * float(np.abs(want).max()) + 1e-6
+        if args.out_dtype != "f32":                # plus one spacing of the 16-bit format at the largest value
+            bound += float(np.abs(want).max()) * (2.0 ** -10 if args.out_dtype == "f16" else 2.0 ** -7)
         cpu = {"value": round(spx / ta[len(ta) // 2] / 1e6, 2), "unit": "Mpixels/s", "cores": nt, "kind": "oracle",
                "sample": "%d image(s) of %s: median of %d runs on %d threads (and of %d runs on one thread), about %.0f s of CPU work" % (sample.shape[0], args.workload, reps_all, nt, reps_one, sum(ta) * nt + sum(to)),
                "value_1_thread": round(spx / to[len(to) // 2] / 1e6, 2)}
@@ -209,11 +215,11 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "H": H, "W": W, "input": dt, "k": K_COARSITY,
-                   "buffer_pairs": n_pairs, "cache": "warm" if args.warm_cache else "cold (rotating buffers)",
+                   "result": args.out_dtype, "buffer_pairs": n_pairs, "cache": "warm" if args.warm_cache else "cold (rotating buffers)",
                    "launch": shape, "workgroups": n_blocks},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": TRAFFIC_BYTES.get(args.workload) if kernel_sources_sha256() == TRAFFIC_SOURCES_SHA256 and not explicit_tuning else None,
+                     "traffic": TRAFFIC_BYTES.get(args.workload) if kernel_sources_sha256() == TRAFFIC_SOURCES_SHA256 and not explicit_tuning and args.out_dtype == "f32" else None,
                      "algorithmic_bytes_per_launch": algo_bytes,
                      "launch_us_avg_over_timed_region": round(launch_us, 3),
                      "launch_us_single_median": round(single_med_us, 3)},

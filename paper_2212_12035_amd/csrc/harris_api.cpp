@@ -60,8 +60,14 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     // Measured, moved against fixed borders: 378 against 393 us on 64x1080x1920 float32, 12.5
     // against 12.8 us on 1536x2560, 37.0 against 37.3 us on 2832x4256, 89 against 93 us on
     // 8192x8192 uint8.
-    if (!(t.flags & (HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_PLAIN_STORES)))
-        t.flags |= can_align ? HARRIS_TUNE_ALIGNED_STORES : HARRIS_TUNE_PLAIN_STORES;
+    // 16-bit results pay more for moved borders (strips of 224 instead of 252 columns): worth it
+    // only for large float32 inputs (64x1080x1920: 341 against 359 us; 1536x2560: 12.8 against
+    // 12.4 us; 8192x8192 uint8: 81 against 74 us).
+    if (!(t.flags & (HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_PLAIN_STORES))) {
+        const long long bytes = (long long)batch * (3LL * H * W * elem_size(dtype) + (long long)out_elem_size(out_dtype) * n * m);
+        const bool align = can_align && (out_dtype == HARRIS_OUT_F32 || (dtype == HARRIS_F32 && bytes > (128LL << 20)));
+        t.flags |= align ? HARRIS_TUNE_ALIGNED_STORES : HARRIS_TUNE_PLAIN_STORES;
+    }
     // As few strips as 64-lane wavefronts allow, all of the same width.  A moved border lies up
     // to one 64-byte block less a lane (12 float32 or 28 16-bit columns) right of the strip's
     // nominal end, and the wavefront must reach that far.

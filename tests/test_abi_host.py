@@ -131,9 +131,14 @@ def test_plan_for_16_bit_results(pkg):
     # 16-bit results: tile kernel only; moved strip borders reach up to 28 columns (64 bytes),
     # so strips are at most 224 columns; the widest lanes need 8-byte aligned result rows.
     F16, BF16 = pkg.HARRIS_OUT_F16, pkg.HARRIS_OUT_BF16
-    shape, blocks = pkg.harris_plan_typed(pkg.HARRIS_F32, F16, 1, 1536, 2560)
+    shape, blocks = pkg.harris_plan_typed(pkg.HARRIS_F32, F16, 64, 1080, 1920)
     assert shape["schedule"] == pkg.HARRIS_SCHEDULE_TILES and shape["px"] == 4 and shape["flags"] & pkg.HARRIS_TUNE_ALIGNED_STORES
-    assert blocks % 12 == 0                                     # ceil(2556 / 224) = 12 strips (11 for float32 results)
+    assert blocks == 64 * 90 * 9                                # ceil(1916 / 224) = 9 strips (8 for float32 results)
+    # small problems and 8-bit input keep the wider strips with fixed borders
+    small, blocks = pkg.harris_plan_typed(pkg.HARRIS_F32, F16, 1, 1536, 2560)
+    assert small["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES and (small["rows"], small["waves_per_block"]) == (8, 9) and blocks == 253
+    assert pkg.harris_plan_typed(pkg.HARRIS_U8, BF16, 1, 8192, 8192)[0]["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES
+    assert pkg.harris_plan_typed(pkg.HARRIS_F32, F16, 1, 1536, 2560, tuning=dict(flags=pkg.HARRIS_TUNE_ALIGNED_STORES))[1] % 12 == 0
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, BF16, 1, 64, 96, out_align=4)[0]["px"] == 2
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, BF16, 1, 64, 96, out_align=2)[0]["px"] == 1
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_F32, 1, 1536, 2560) == pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
