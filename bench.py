@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "e4aa39043dfa37c97c390108a27a5f0c475e4bb98230f19da7a616c584cdbae1"
-TRAFFIC_BYTES = {"noise_f32_1536x2560": 65128872, "rects_f32_64x1080x1920": 2173367988,
-                 "blobs_f32_2832x4256": 199659820, "noise_u8_8192x8192": 485619564}
+TRAFFIC_SOURCES_SHA256 = "83b94c3c9e93a89569b6f715f5d28e483af4c882e6f14347631e2d293f9c9520"
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 65133082, "rects_f32_64x1080x1920": 2196455228,
+                 "blobs_f32_2832x4256": 199693972, "noise_u8_8192x8192": 489600862}
 
 
 def kernel_sources_sha256():

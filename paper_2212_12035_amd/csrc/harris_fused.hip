@@ -493,7 +493,10 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
         const uint32_t bytes = (j < out_rows && b1 > b0) ? (b1 - b0) << esh : 0u;
         out_rs[j] = make_rsrc(reinterpret_cast<const void*>(row_addr + ((size_t)b0 << esh)), bytes);
         out_lead[j] = (sx0 - b0) << esh;
+        asm volatile("" : "+s"(out_lead[j]));                   // finished here, not next to the store
     });
+    uint32_t lane_bytes = (lane * PX) << esh;
+    asm volatile("" : "+v"(lane_bytes));
     __builtin_amdgcn_sched_barrier(0);
 
     LineBuffers<PX> lb;
@@ -537,8 +540,7 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 
     // The last wavefront skips the four rows it has no data for.
     __builtin_amdgcn_sched_barrier(0);
-    const uint32_t lane_bytes = (lane * PX) << esh;
-    if (p.out_kind == HARRIS_OUT_F32) {
+    if (__builtin_expect(p.out_kind == HARRIS_OUT_F32, 1)) {
         static_for<0, RW>([&](auto jj) {
             constexpr int j = decltype(jj)::value;
             if (j < RW - 4 || wave + 1 < n_waves) store_row<PX>(results[j], out_rs[j], lane_bytes + out_lead[j]);
