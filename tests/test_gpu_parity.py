@@ -408,6 +408,56 @@ def test_16_bit_results_layouts_and_overflow(gpu, oracle):
     assert e.value.status == -3
 
 
+# ---------------------------------------------------------------- seeded random shapes, layouts and launch shapes
+
+def test_random_shapes_layouts_and_launch_shapes(gpu, oracle):
+    # 60 seeded cases over everything a caller can vary at once: batch, height, width (any
+    # residue modulo 4), input and result type, Sobel scale, window, k, row padding and base
+    # offsets of both arrays (so every lane width and every phase of a moved strip border
+    # occurs), and a launch shape drawn from the valid ones.  Guard bands and padding must stay
+    # untouched.
+    import torch
+    rng = np.random.default_rng(20221212)
+    for case in range(60):
+        B = int(rng.integers(1, 4)); H = int(rng.integers(5, 70)); W = int(rng.choice([rng.integers(5, 40), rng.integers(40, 300), rng.integers(300, 800)]))
+        if rng.random() < 0.5:
+            W = max(8, W // 4 * 4)                                   # half of the cases on the 16-byte path
+        u8 = bool(rng.random() < 0.35)
+        fmt = str(rng.choice(["f32", "f32", "f16", "bf16"]))
+        scale = float(rng.choice([1.0, S12])); window = int(rng.integers(0, 2)); k = float(rng.choice([0.04, 0.06, 0.15]))
+        n, m = H - 4, W - 4
+        in_pitch = W + int(rng.choice([0, 0, 4, 7, 12])); in_off = int(rng.choice([0, 0, 4, 1, 16]))
+        out_pitch = m + int(rng.choice([0, 0, 4, 5, 8, 28])); out_off = int(rng.choice([0, 0, 4, 2, 8, 12, 20]))
+        rgb = hi.white_noise_u8(1000 + case, B, H, W) if u8 else hi.rectangles_f32(1000 + case, B, H, W, n_rect=12)
+        store = torch.zeros(B * 3 * H * in_pitch + 64, dtype=torch.uint8 if u8 else torch.float32, device="cuda")
+        src = store[in_off:in_off + B * 3 * H * in_pitch].view(B, 3, H, in_pitch)[:, :, :, :W]
+        src.copy_(torch.from_numpy(rgb).cuda())
+        tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[fmt]
+        flat = torch.full((B * n * out_pitch + 64,), float("nan"), dtype=tdt, device="cuda")
+        view = flat[out_off:out_off + B * n * out_pitch].view(B, n, out_pitch)[:, :, :m]
+        tune = None
+        r = rng.random()
+        if r < 0.3:
+            tune = dict(schedule=2, rows=int(rng.choice([4, 8])), waves_per_block=int(rng.integers(2, 9)))
+        elif r < 0.45 and fmt == "f32":
+            tune = dict(schedule=1, rows=int(rng.integers(1, 40)), prefetch=int(rng.choice([2, 3, 6])), waves_per_block=int(rng.choice([1, 2, 4])))
+        say("case random %d: %s %dx3x%dx%d -> %s scale=%g window=%d k=%g pitches %d/%d offsets %d/%d tuning %s"
+            % (case, "u8" if u8 else "f32", B, H, W, fmt, scale, window, k, in_pitch, out_pitch, in_off, out_off, tune))
+        gpu.harris_coarsity_typed(src, view, k, scale, window, tuning=tune)
+        torch.cuda.synchronize()
+        want = oracle.harris(rgb, k, scale, window)
+        got = view.float().cpu().numpy()
+        bound = 1e-4 * float(np.abs(want).max()) + 1e-6
+        if fmt == "f32":
+            check(got, want)
+        else:
+            want16 = _as_f32(oracle.round_to_16bit(want, fmt), fmt)
+            assert np.all(np.abs(got.astype(np.float64) - want16) <= bound + _ulp16(want, fmt))
+        rest = flat.clone()
+        rest[out_off:out_off + B * n * out_pitch].view(B, n, out_pitch)[:, :, :m] = float("nan")
+        assert bool(torch.isnan(rest).all())
+
+
 # ---------------------------------------------------------------- unfused kernel groupings (baselines)
 
 @pytest.mark.parametrize("grouping", [1, 2, 3, 4])
