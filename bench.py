@@ -27,19 +27,25 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
-# for the kernel sources they were taken with: (sha256 of the csrc files, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "83b94c3c9e93a89569b6f715f5d28e483af4c882e6f14347631e2d293f9c9520"
+# for the kernel sources they were taken with: (sha256 of the csrc files without comments, {workload: bytes}).
+TRAFFIC_SOURCES_SHA256 = "ad77811986bdd357c2a788c29299053f9e1905de08125c211a8bf56733986fc3"
 TRAFFIC_BYTES = {"noise_f32_1536x2560": 65133082, "rects_f32_64x1080x1920": 2196455228,
                  "blobs_f32_2832x4256": 199693972, "noise_u8_8192x8192": 489600862}
 
 
 def kernel_sources_sha256():
+    """Hash of the kernel sources without comments and blank lines: what the compiler sees."""
     import hashlib
+    import re
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2212_12035_amd", "csrc")
     for name in sorted(os.listdir(csrc)):
-        with open(os.path.join(csrc, name), "rb") as f:
-            h.update(name.encode() + b"\0" + f.read())
+        with open(os.path.join(csrc, name), "r") as f:
+            text = f.read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", "", text)
+        text = "\n".join(line.rstrip() for line in text.splitlines() if line.strip())
+        h.update(name.encode() + b"\0" + text.encode())
     return h.hexdigest()
 WORKLOAD = "noise_f32_1536x2560"
 K_COARSITY = 0.04

@@ -7,28 +7,31 @@
 // section 4.3 is the idea of a pipeline over image lines with separated 3x3
 // kernels and rotating registers, re-cut for a 64-lane wavefront:
 //
-//  * A wavefront owns a vertical strip of the image and walks it row by row.
-//    Lane l holds PX adjacent columns; one row of one plane is a single coalesced
-//    load of 64*PX elements (128 bits per lane for float32 at PX = 4).
+//  * A wavefront owns a vertical strip of the image.  Lane l holds PX adjacent
+//    columns; one row of one plane is a single coalesced load of 64*PX elements
+//    (128 bits per lane for float32 at PX = 4).
 //  * Vertical taps never touch memory: the last two gray rows and the last two
-//    rows of (Ix^2, Ix*Iy, Iy^2) live in registers ("register rotation").  The loop
-//    is unrolled by a multiple of 3, so the rotation is a renaming, not a copy.
+//    rows of (Ix^2, Ix*Iy, Iy^2) live in registers ("register rotation").  Row steps
+//    are unrolled, so the rotation is a renaming, not a copy.
 //  * Both 3x3 stages are separated (section 4.3, "Convolution Separation"):
 //    [1 2 1]^T/[-1 0 1]^T down the column from registers first, then the horizontal
 //    taps.  Horizontal neighbours come from the lane to the right through a DPP
 //    wave shift; each stage consumes two columns from the right, so a lane's
 //    output columns start at the lane's own first input column and the result row
 //    is stored with aligned vector stores.
-//  * Wavefronts share nothing (no LDS, no barrier).  The strip of a wavefront
-//    overlaps its right neighbour by the 4-column halo; the last lane(s) only
-//    supply that halo.
-//  * Several input rows per wavefront are kept in flight (a register queue of
-//    D rows), so that memory latency is covered even at one wavefront per SIMD.
-//  * The image is cut into bands of R output rows; a band re-reads the 4 halo
-//    rows of its neighbour.  Odd bands walk upwards, so two neighbouring bands
-//    begin (or end) on the same rows at the same time and the second read hits
-//    in L2; tiles are dealt to workgroups so that each XCD (own L2) gets one
-//    contiguous run of tiles.
+//  * The strip of a wavefront overlaps its right neighbour by the 4-column halo;
+//    the last lane(s) only supply that halo.
+//
+// Two schedules run this pipeline:
+//  * Tiles (the default, harris_tile_kernel): a workgroup of NW wavefronts takes NW*RW
+//    input rows of one strip; every wavefront requests its RW rows at once, hands its
+//    first four gray rows to the wavefront above through LDS (one barrier), and
+//    stores its RW result rows in one burst at the end.
+//  * Bands (harris_fused_kernel): one long-lived wavefront walks a band of R result
+//    rows with a register queue of D input rows in flight; no LDS, no barrier.  Odd
+//    bands walk upwards, so two neighbouring bands begin on the rows they share.
+// In both, tiles are dealt to workgroups so that each XCD (own L2) gets one
+// contiguous run of tiles.
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -397,7 +400,7 @@ __device__ __forceinline__ void pin_values(float (&v)[PX]) {
 
 // ---------------------------------------------------------------- the tile kernel
 //
-// Second schedule, for images too small to keep long-lived wavefronts busy: a
+// The default schedule: a
 // workgroup of NW wavefronts owns a tile of NW*RW input rows of one strip, and every
 // wavefront requests its RW rows (3*RW loads) at once, so no wavefront goes through a
 // chain of dependent memory round trips.  Wavefront w turns its rows into gray,
