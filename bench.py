@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files without comments, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "ad77811986bdd357c2a788c29299053f9e1905de08125c211a8bf56733986fc3"
+TRAFFIC_SOURCES_SHA256 = "767a808b1f681911a5efc9255f9fe32898562da7993aef32e4f4f281e21f68e8"
 TRAFFIC_BYTES = {"noise_f32_1536x2560": 65133082, "rects_f32_64x1080x1920": 2196455228,
                  "blobs_f32_2832x4256": 199693972, "noise_u8_8192x8192": 489600862}
 
@@ -185,6 +185,31 @@ def main():
         step(0)                                   # pair 0 holds the fused kernel's result again
         torch.cuda.synchronize(dev)
 
+    # What a kernel that only moves these bytes reaches on this GPU: the library's streaming-copy
+    # probe (three planes in, one float per result pixel out) on the same rotating buffers.
+    probe = None
+    if args.out_dtype == "f32":
+        probe_bytes = B * n * m * (3 * (1 if is_u8 else 4) + 4)
+        reps = max(20, min(400, args.steps // 4))
+        def pstep(i):
+            a, o = calls[i % n_pairs]
+            rc = lib.harris_probe_copy(a, dtype_code, B, H, W, o, sptr)
+            if rc != 0:
+                raise RuntimeError(pkg.harris_strerror(rc))
+        for i in range(max(3, reps // 4)):
+            pstep(i)
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0.record(stream)
+        for i in range(reps):
+            pstep(i)
+        p1.record(stream)
+        torch.cuda.synchronize(dev)
+        probe_us = p0.elapsed_time(p1) * 1e3 / reps
+        probe = {"us": round(probe_us, 3), "bytes": probe_bytes, "GB/s": round(probe_bytes / (probe_us * 1e-6) / 1e9, 1),
+                 "what": "harris_probe_copy: reads 3 planes, writes 1 float per result pixel, nothing else"}
+        step(0)                                   # pair 0 holds the fused kernel's result again
+        torch.cuda.synchronize(dev)
+
     # Correctness of what was timed: pair 0 against the oracle (also the CPU baseline).
     got = outs[0].float().cpu().numpy()
     cpu = None
@@ -228,7 +253,9 @@ def main():
                      "traffic": TRAFFIC_BYTES.get(args.workload) if kernel_sources_sha256() == TRAFFIC_SOURCES_SHA256 and not explicit_tuning and args.out_dtype == "f32" else None,
                      "algorithmic_bytes_per_launch": algo_bytes,
                      "launch_us_avg_over_timed_region": round(launch_us, 3),
-                     "launch_us_single_median": round(single_med_us, 3)},
+                     "launch_us_single_median": round(single_med_us, 3),
+                     "frac_of_copy_probe": round(achieved / probe["GB/s"], 4) if probe else None},
+        "copy_probe": probe,
         "cpu_baseline": cpu,
         "kernel_groupings": groupings,
         "max_abs_err_vs_oracle": max_err, "err_bound": bound,

@@ -226,6 +226,17 @@ int harris_coarsity_grouped(const void* rgb, int dtype, int batch, int H, int W,
 /* Workspace bytes harris_coarsity_grouped needs; 0 for grouping 4; -1 for invalid arguments. Host only. */
 long long harris_grouped_workspace_bytes(int grouping, int batch, int H, int W);
 
+/*
+ * Measurement aid, not the Harris operator: a plain streaming kernel with the traffic of one
+ * Harris launch.  For every image it reads the first (H-4)*(W-4) elements of each of the three
+ * planes (taken as flat arrays) and writes their sum as float32 to out[b][i]: 3*e + 4 bytes per
+ * result pixel, e = 4 or 1, against the 3*e*H*W + 4*(H-4)*(W-4) of the operator.  Its duration
+ * beside harris_coarsity's shows what this read/write mix reaches on the GPU at hand.
+ * Requires dense arrays, 16-byte aligned rgb and out, H*W*e and (H-4)*(W-4)*4 multiples of 16,
+ * batch <= 65535 (else HARRIS_ERR_ARG / HARRIS_ERR_SHAPE); arguments otherwise as harris_coarsity.
+ */
+int harris_probe_copy(const void* rgb, int dtype, int batch, int H, int W, float* out, void* stream);
+
 /* Static, NUL-terminated description of a harris_status value. */
 const char* harris_strerror(int status);
 

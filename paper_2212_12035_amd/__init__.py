@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     HARRIS_OUT_F32, HARRIS_OUT_F16, HARRIS_OUT_BF16, harris_coarsity_typed, harris_plan_typed,
     HarrisError, HarrisTuning, HarrisLayout, library_path, load_library, harris_coarsity_pitched,
     harris_coarsity, harris_coarsity_u8, harris_coarsity_ex, harris_plan, harris_strerror, harris_version,
-    harris_coarsity_grouped, harris_grouped_workspace_bytes,
+    harris_coarsity_grouped, harris_grouped_workspace_bytes, harris_probe_copy,
 )

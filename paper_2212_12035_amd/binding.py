@@ -22,7 +22,7 @@ _LIB_PATH = os.path.join(_HERE, "libharris.so")
 #: every symbol include/harris.h declares
 EXPORTS = ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan", "harris_plan_typed",
            "harris_coarsity_pitched", "harris_coarsity_typed", "harris_coarsity_grouped",
-           "harris_grouped_workspace_bytes", "harris_strerror", "harris_version")
+           "harris_grouped_workspace_bytes", "harris_probe_copy", "harris_strerror", "harris_version")
 HARRIS_OUT_F32, HARRIS_OUT_F16, HARRIS_OUT_BF16 = 0, 1, 2
 
 
@@ -83,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     lib.harris_coarsity_grouped.argtypes = [vp, ci, ci, ci, ci, cf, cf, ci, ci, vp, ctypes.c_longlong, vp, vp]
     lib.harris_grouped_workspace_bytes.argtypes = [ci, ci, ci, ci]
     lib.harris_grouped_workspace_bytes.restype = ctypes.c_longlong
+    lib.harris_probe_copy.argtypes = [vp, ci, ci, ci, ci, vp, vp]
+    lib.harris_probe_copy.restype = ci
     for name in ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan", "harris_version",
                  "harris_coarsity_grouped"):
         getattr(lib, name).restype = ci
@@ -223,6 +225,18 @@ def harris_coarsity_typed(rgb, out, k: float = 0.04, sobel_scale: float = 1.0, w
         _check(load_library().harris_coarsity_typed(rgb.data_ptr(), dtype, B, H, W, ctypes.byref(lay), k, sobel_scale, window,
                                                     out.data_ptr(), kinds[out.dtype], _tuning_arg(tuning),
                                                     _stream_ptr(stream, rgb.device)))
+    return out
+
+
+def harris_probe_copy(rgb, out=None, stream=None):
+    """The streaming-copy probe: out[b][i] = sum over the three planes of their i-th element, i < (H-4)*(W-4)."""
+    import torch
+    if not isinstance(rgb, torch.Tensor) or rgb.dtype not in (torch.float32, torch.uint8):
+        raise TypeError("rgb must be a float32 or uint8 torch tensor")
+    B, H, W, out = _prepare(rgb, out, rgb.dtype)
+    dtype = HARRIS_U8 if rgb.dtype == torch.uint8 else HARRIS_F32
+    with torch.cuda.device(rgb.device):
+        _check(load_library().harris_probe_copy(rgb.data_ptr(), dtype, B, H, W, out.data_ptr(), _stream_ptr(stream, rgb.device)))
     return out
 
 

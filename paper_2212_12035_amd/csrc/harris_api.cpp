@@ -310,6 +310,17 @@ int harris_coarsity_grouped(const void* rgb, int dtype, int batch, int H, int W,
                                          grouping, static_cast<float*>(workspace), out, stream);
 }
 
+int harris_probe_copy(const void* rgb, int dtype, int batch, int H, int W, float* out, void* stream) {
+    if (dtype != HARRIS_F32 && dtype != HARRIS_U8) return HARRIS_ERR_ARG;
+    if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
+    if (batch == 0 || H == 4 || W == 4) return HARRIS_OK;
+    if (rgb == nullptr || out == nullptr) return HARRIS_ERR_NULL;
+    const long long e = elem_size(dtype);
+    if (pointer_alignment(rgb) < 16 || pointer_alignment(out) < 16) return HARRIS_ERR_ARG;
+    if (((long long)H * W * e) % 16 != 0 || ((long long)(H - 4) * (W - 4) * 4) % 16 != 0) return HARRIS_ERR_ARG;
+    return harris_launch::launch_copy_probe(rgb, dtype, batch, H, W, out, stream);
+}
+
 const char* harris_strerror(int status) {
     switch (status) {
         case HARRIS_OK: return "success";

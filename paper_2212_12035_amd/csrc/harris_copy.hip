@@ -1,0 +1,116 @@
+// Measurement aid, not part of the Harris operator: a plain streaming kernel that moves
+// (almost exactly) the bytes one Harris launch has to move -- it reads (H-4)*(W-4) elements of
+// each of the three planes of every image and writes one float per result pixel, their sum --
+// and does nothing else.  Timed beside the fused kernel it shows what a kernel with this
+// read/write mix reaches on the GPU at hand, as opposed to the published peak.
+//
+// Planes are taken as flat arrays.  float32: a wavefront moves two chunks of 256 elements (4
+// per lane, 128-bit loads and stores; the fastest of 1, 2 and 4 chunks measured).  uint8: one
+// chunk of 1024 elements (one 128-bit load per lane and plane, a turn through LDS, four 128-bit
+// stores of a contiguous kilobyte each).  All
+// loads come before the first store, everything is non-temporal and goes through buffer
+// descriptors, so that the tail needs no branch.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "harris.h"
+#include "harris_launch.h"
+
+namespace {
+
+constexpr int kNonTemporal = 2;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+
+// float32: a chunk is 256 elements, 4 per lane.
+template <int kRun>
+__global__ __launch_bounds__(256) void copy_probe_f32(const float* rgb, float* out, unsigned long long count, unsigned long long plane,
+                                                      unsigned long long chunks_per_image) {
+    const unsigned lane = threadIdx.x % 64;
+    const unsigned long long wave = (unsigned long long)blockIdx.x * 4 + threadIdx.x / 64;
+    const float* src = rgb + (unsigned long long)blockIdx.y * 3 * plane;
+    float* dst = out + (unsigned long long)blockIdx.y * count;
+    u32x4 v[kRun][3];
+    unsigned long long chunk[kRun];
+    uint32_t live[kRun];                                        // elements of the chunk inside the image
+#pragma unroll
+    for (int r = 0; r < kRun; ++r) {
+        chunk[r] = wave * kRun + r;
+        const bool inside = chunk[r] < chunks_per_image;
+        if (!inside) chunk[r] = 0;
+        const unsigned long long left = count - chunk[r] * 256;
+        live[r] = inside ? (uint32_t)(left < 256 ? left : 256) : 0u;
+#pragma unroll
+        for (int c = 0; c < 3; ++c)
+            v[r][c] = __builtin_amdgcn_raw_buffer_load_b128(rsrc(src + c * plane + chunk[r] * 256, live[r] * 4u), lane * 16u, 0, kNonTemporal);
+    }
+#pragma unroll
+    for (int r = 0; r < kRun; ++r) {
+        u32x4 w;
+        w.x = __float_as_uint(__uint_as_float(v[r][0].x) + __uint_as_float(v[r][1].x) + __uint_as_float(v[r][2].x));
+        w.y = __float_as_uint(__uint_as_float(v[r][0].y) + __uint_as_float(v[r][1].y) + __uint_as_float(v[r][2].y));
+        w.z = __float_as_uint(__uint_as_float(v[r][0].z) + __uint_as_float(v[r][1].z) + __uint_as_float(v[r][2].z));
+        w.w = __float_as_uint(__uint_as_float(v[r][0].w) + __uint_as_float(v[r][1].w) + __uint_as_float(v[r][2].w));
+        __builtin_amdgcn_raw_buffer_store_b128(w, rsrc(dst + chunk[r] * 256, live[r] * 4u), lane * 16u, 0, kNonTemporal);
+    }
+}
+
+// uint8: a chunk is 1024 elements.  A lane loads 16 of them per plane with one 128-bit load; the
+// wavefront then turns its 3 x 1 KB around in a private piece of LDS so that lane l holds elements
+// 256 q + 4 l .. + 3 for q = 0..3, and each of its four 128-bit stores writes one contiguous kilobyte
+// (stores of 16 bytes per lane at a stride of 64 bytes were measured 4 times slower).
+__global__ __launch_bounds__(256) void copy_probe_u8(const uint8_t* rgb, float* out, unsigned long long count, unsigned long long plane,
+                                                     unsigned long long chunks_per_image) {
+    __shared__ uint32_t turn[4][3][256];                       // [wavefront][plane][dword of the chunk]
+    const unsigned lane = threadIdx.x % 64, wv = threadIdx.x / 64;
+    unsigned long long chunk = (unsigned long long)blockIdx.x * 4 + wv;
+    const uint8_t* src = rgb + (unsigned long long)blockIdx.y * 3 * plane;
+    float* dst = out + (unsigned long long)blockIdx.y * count;
+    const bool inside = chunk < chunks_per_image;
+    if (!inside) chunk = 0;
+    const unsigned long long left = count - chunk * 1024;
+    const uint32_t live = inside ? (uint32_t)(left < 1024 ? left : 1024) : 0u;
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc(src + c * plane + chunk * 1024, live), lane * 16u, 0, kNonTemporal);
+        *reinterpret_cast<u32x4*>(&turn[wv][c][4 * lane]) = v;
+    }
+    // Only this wavefront reads what it wrote, and LDS operations of one wavefront complete in
+    // order; the fences keep the compiler from moving a lane's reads above the other lanes' writes.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const __amdgpu_buffer_rsrc_t drs = rsrc(dst + chunk * 1024, live * 4u);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t a = turn[wv][0][64 * q + lane], b = turn[wv][1][64 * q + lane], c = turn[wv][2][64 * q + lane];
+        u32x4 w;
+        w.x = __float_as_uint((float)((a & 0xffu) + (b & 0xffu) + (c & 0xffu)));
+        w.y = __float_as_uint((float)(((a >> 8) & 0xffu) + ((b >> 8) & 0xffu) + ((c >> 8) & 0xffu)));
+        w.z = __float_as_uint((float)(((a >> 16) & 0xffu) + ((b >> 16) & 0xffu) + ((c >> 16) & 0xffu)));
+        w.w = __float_as_uint((float)((a >> 24) + (b >> 24) + (c >> 24)));
+        __builtin_amdgcn_raw_buffer_store_b128(w, drs, 1024u * q + lane * 16u, 0, kNonTemporal);
+    }
+}
+
+}  // namespace
+
+namespace harris_launch {
+
+int launch_copy_probe(const void* rgb, int dtype, int batch, int H, int W, float* out, void* stream) {
+    const unsigned long long count = (unsigned long long)(H - 4) * (W - 4), plane = (unsigned long long)H * W;
+    const unsigned long long per_chunk = dtype == HARRIS_U8 ? 1024 : 256, run = dtype == HARRIS_U8 ? 1 : 2;
+    const unsigned long long chunks = (count + per_chunk - 1) / per_chunk, waves = (chunks + run - 1) / run, blocks = (waves + 3) / 4;
+    if (blocks > 0x7fffffffULL || batch > 65535) return HARRIS_ERR_SHAPE;
+    const dim3 grid((unsigned)blocks, (unsigned)batch), block(256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dtype == HARRIS_U8) hipLaunchKernelGGL(copy_probe_u8, grid, block, 0, s, static_cast<const uint8_t*>(rgb), out, count, plane, chunks);
+    else hipLaunchKernelGGL((copy_probe_f32<2>), grid, block, 0, s, static_cast<const float*>(rgb), out, count, plane, chunks);
+    return hipGetLastError() == hipSuccess ? HARRIS_OK : HARRIS_ERR_LAUNCH;
+}
+
+}  // namespace harris_launch

@@ -80,6 +80,9 @@ size_t grouped_workspace_floats(int grouping, int batch, int H, int W);
 int launch_grouped(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale, int binomial,
                    int grouping, float* workspace, float* out, void* stream);
 
+// Enqueue the streaming-copy probe (see harris_probe_copy).  Returns a harris_status.
+int launch_copy_probe(const void* rgb, int dtype, int batch, int H, int W, float* out, void* stream);
+
 }  // namespace harris_launch
 
 #endif

@@ -154,6 +154,18 @@ def test_plan_for_16_bit_results(pkg):
     assert lib.harris_coarsity_typed(None, 0, 0, 64, 64, None, 0.04, 1.0, 0, None, 2, None, None) == 0
 
 
+def test_copy_probe_validates_its_arguments(pkg):
+    lib = pkg.load_library()
+    one = ctypes.c_void_p(4096)
+    assert lib.harris_probe_copy(None, 0, 1, 64, 64, one, None) == -1
+    assert lib.harris_probe_copy(one, 2, 1, 64, 64, one, None) == -3
+    assert lib.harris_probe_copy(one, 0, 1, 3, 64, one, None) == -2
+    assert lib.harris_probe_copy(ctypes.c_void_p(4100), 0, 1, 64, 64, one, None) == -3      # rgb not 16-byte aligned
+    assert lib.harris_probe_copy(one, 1, 1, 5, 7, one, None) == -3                           # planes of 35 bytes
+    assert lib.harris_probe_copy(one, 0, 1, 9, 11, one, None) == -3                          # 35 results: rows of images not 16-byte multiples
+    assert lib.harris_probe_copy(None, 0, 0, 64, 64, None, None) == 0
+
+
 def test_index_division_by_multiplication_is_exact(tmp_path):
     # The tile kernel splits its workgroup index with a multiply-high division whose constants
     # the host computes; the same header functions are checked here against the hardware division.

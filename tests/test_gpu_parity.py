@@ -458,6 +458,29 @@ def test_random_shapes_layouts_and_launch_shapes(gpu, oracle):
         assert bool(torch.isnan(rest).all())
 
 
+# ---------------------------------------------------------------- the streaming-copy probe (measurement aid)
+
+def test_copy_probe_moves_what_it_says(gpu):
+    # Not the Harris operator: out[b][i] = R[i] + G[i] + B[i] over the first (H-4)*(W-4) elements of
+    # the flat planes.  Exact in float32 for these inputs (sums of three small integers or of
+    # multiples of 2^-10), several chunks per wavefront and a ragged last chunk.
+    import torch
+    for B, H, W, u8 in ((2, 36, 260, False), (1, 12, 8, False), (3, 40, 1028, True), (1, 68, 132, True)):
+        rng = np.random.default_rng(H * W)
+        if u8:
+            rgb = rng.integers(0, 256, size=(B, 3, H, W), dtype=np.uint8)
+        else:
+            rgb = (rng.integers(0, 1024, size=(B, 3, H, W)) / 1024.0).astype(np.float32)
+        n = (H - 4) * (W - 4)
+        flat = rgb.reshape(B, 3, H * W).astype(np.float32)
+        want = (flat[:, 0, :n] + flat[:, 1, :n] + flat[:, 2, :n]).reshape(B, H - 4, W - 4)
+        say("case copy probe %s %dx3x%dx%d" % ("u8" if u8 else "f32", B, H, W))
+        out = torch.full((B, H - 4, W - 4), float("nan"), device="cuda")
+        gpu.harris_probe_copy(torch.from_numpy(rgb).cuda(), out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), want)
+
+
 # ---------------------------------------------------------------- unfused kernel groupings (baselines)
 
 @pytest.mark.parametrize("grouping", [1, 2, 3, 4])
