@@ -29,8 +29,8 @@ HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files without comments, {workload: bytes}).
 TRAFFIC_SOURCES_SHA256 = "767a808b1f681911a5efc9255f9fe32898562da7993aef32e4f4f281e21f68e8"
-TRAFFIC_BYTES = {"noise_f32_1536x2560": 65133082, "rects_f32_64x1080x1920": 2196455228,
-                 "blobs_f32_2832x4256": 199693972, "noise_u8_8192x8192": 489600862}
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 65144452, "rects_f32_64x1080x1920": 2197355128,
+                 "blobs_f32_2832x4256": 199674623, "noise_u8_8192x8192": 489242307}
 
 
 def kernel_sources_sha256():
