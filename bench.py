@@ -70,8 +70,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-groupings", action="store_true", help="skip timing the unfused kernel groupings")
     ap.add_argument("--warm-cache", action="store_true", help="reuse one buffer pair (cache-resident; not the roofline number)")
-    ap.add_argument("--out-dtype", choices=("f32", "f16", "bf16"), default="f32",
-                    help="type the result is stored in (the arithmetic stays float32); not the headline configuration")
+    ap.add_argument("--out-dtype", choices=("f32", "f16", "bf16", "u8"), default="f32",
+                    help="type the result is stored in (the arithmetic stays float32; u8: codes rint(v + 128) clamped); "
+                         "not the headline configuration")
     return ap.parse_args()
 
 
@@ -97,9 +98,10 @@ def main():
     host = harris_inputs.make(args.workload)
     n, m = H - 4, W - 4
     in_bytes = B * 3 * H * W * (1 if is_u8 else 4)
-    out_torch = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.out_dtype]
-    out_code = {"f32": pkg.HARRIS_OUT_F32, "f16": pkg.HARRIS_OUT_F16, "bf16": pkg.HARRIS_OUT_BF16}[args.out_dtype]
-    out_bytes = B * n * m * (4 if args.out_dtype == "f32" else 2)
+    out_torch = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "u8": torch.uint8}[args.out_dtype]
+    out_code = {"f32": pkg.HARRIS_OUT_F32, "f16": pkg.HARRIS_OUT_F16, "bf16": pkg.HARRIS_OUT_BF16, "u8": pkg.HARRIS_OUT_U8}[args.out_dtype]
+    out_bytes = B * n * m * {"f32": 4, "f16": 2, "bf16": 2, "u8": 1}[args.out_dtype]
+    Q_SCALE, Q_OFFSET = 1.0, 128.0
     algo_bytes = in_bytes + out_bytes                      # each input element read once, each result written once
     pixels = B * H * W
 
@@ -124,7 +126,10 @@ def main():
 
     def step(i):
         a, o = calls[i % n_pairs]
-        rc = fn(a, dtype_code, B, H, W, None, K_COARSITY, 1.0, 0, o, out_code, tref, sptr)
+        if args.out_dtype == "u8":
+            rc = lib.harris_coarsity_quantized(a, dtype_code, B, H, W, None, K_COARSITY, 1.0, 0, Q_SCALE, Q_OFFSET, o, tref, sptr)
+        else:
+            rc = fn(a, dtype_code, B, H, W, None, K_COARSITY, 1.0, 0, o, out_code, tref, sptr)
         if rc != 0:
             raise RuntimeError(pkg.harris_strerror(rc))
 
@@ -228,10 +233,13 @@ def main():
         for _ in range(reps_one):
             s = time.perf_counter(); harris_oracle.harris(sample, K_COARSITY, nthreads=1); to.append(time.perf_counter() - s)
         ta.sort(); to.sort()
-        max_err = float(np.abs(got[:sample.shape[0]] - want).max())
         bound = 1e-4 * float(np.abs(want).max()) + 1e-6
-        if args.out_dtype != "f32":                # plus one spacing of the 16-bit format at the largest value
+        if args.out_dtype == "u8":                 # codes against the oracle's codes: the bar in codes, plus one
+            want = harris_oracle.quantize_u8(want, Q_SCALE, Q_OFFSET).astype(np.float32)
+            bound = float(np.ceil(bound * abs(Q_SCALE))) + 1.0
+        elif args.out_dtype != "f32":              # plus one spacing of the 16-bit format at the largest value
             bound += float(np.abs(want).max()) * (2.0 ** -10 if args.out_dtype == "f16" else 2.0 ** -7)
+        max_err = float(np.abs(got[:sample.shape[0]] - want).max())
         cpu = {"value": round(spx / ta[len(ta) // 2] / 1e6, 2), "unit": "Mpixels/s", "cores": nt, "kind": "oracle",
                "sample": "%d image(s) of %s: median of %d runs on %d threads (and of %d runs on one thread), about %.0f s of CPU work" % (sample.shape[0], args.workload, reps_all, nt, reps_one, sum(ta) * nt + sum(to)),
                "value_1_thread": round(spx / to[len(to) // 2] / 1e6, 2)}

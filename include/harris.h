@@ -170,7 +170,8 @@ int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W,
 typedef enum harris_out_dtype {
     HARRIS_OUT_F32 = 0,      /* float32, as the thesis's pipeline produces it                     */
     HARRIS_OUT_F16 = 1,      /* IEEE binary16                                                     */
-    HARRIS_OUT_BF16 = 2      /* bfloat16                                                          */
+    HARRIS_OUT_BF16 = 2,     /* bfloat16                                                          */
+    HARRIS_OUT_U8 = 3        /* 8-bit codes; only through harris_coarsity_quantized               */
 } harris_out_dtype;
 
 /*
@@ -180,7 +181,7 @@ typedef enum harris_out_dtype {
  * result type when it is stored: to nearest, ties to even, values beyond the largest finite
  * number to infinity (binary16 overflows from 65520 on: with sobel_scale 1 and inputs in [0, 1]
  * results stay below that; larger inputs may not).
- *   out        device, element type given by out_dtype (a harris_out_dtype), [batch][H-4][W-4]
+ *   out        device, element type given by out_dtype (HARRIS_OUT_F32, _F16 or _BF16), [batch][H-4][W-4]
  *              with the pitches of `layout` counted in result elements; fully overwritten
  *   tuning     as in harris_coarsity_ex, but 16-bit results exist only in HARRIS_SCHEDULE_TILES
  *              (else HARRIS_ERR_ARG); with aligned stores their strips are at most 224 columns
@@ -189,6 +190,20 @@ typedef enum harris_out_dtype {
 int harris_coarsity_typed(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
                           float k, float sobel_scale, int window, void* out, int out_dtype,
                           const harris_tuning* tuning, void* stream);
+
+/*
+ * 8-bit result, 1 byte per pixel instead of 4: every coarsity value v (float32, computed as by
+ * the other entry points) is stored as the code
+ *     clamp(round_to_nearest_even(fma(v, q_scale, q_offset)), 0, 255)
+ * with the multiply-add rounded once, in float32; NaN gives 0.  (An extension: the thesis's
+ * arrays are float32 and it defines no such code; q_scale and q_offset are the caller's.)
+ *   out   device, uint8 [batch][H-4][W-4], pitches of `layout` in bytes; fully overwritten
+ * Tile schedule only (else HARRIS_ERR_ARG), q_scale and q_offset finite (else HARRIS_ERR_ARG).
+ * The fastest path needs 4-byte aligned result rows and W % 4 == 0.
+ */
+int harris_coarsity_quantized(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
+                              float k, float sobel_scale, int window, float q_scale, float q_offset,
+                              uint8_t* out, const harris_tuning* tuning, void* stream);
 
 /*
  * The launch shape harris_coarsity_ex would use for this problem (after applying

@@ -59,6 +59,8 @@ def _load():
         for name in ("harris_ref_round_binary16", "harris_ref_round_bfloat16"):
             getattr(lib, name).argtypes = [_f32p, ctypes.c_longlong, ctypes.POINTER(ctypes.c_uint16)]
             getattr(lib, name).restype = None
+        lib.harris_ref_quantize_u8.argtypes = [_f32p, ctypes.c_longlong, cf, cf, _u8p]
+        lib.harris_ref_quantize_u8.restype = None
         lib.harris_ref_hardware_threads.restype = ci
         _lib = lib
     return _lib
@@ -168,4 +170,12 @@ def round_to_16bit(values: np.ndarray, fmt: str) -> np.ndarray:
     out = np.empty(a.shape, dtype=np.uint16)
     fn = {"f16": "harris_ref_round_binary16", "bf16": "harris_ref_round_bfloat16"}[fmt]
     getattr(_load(), fn)(_ptr(a), a.size, out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)))
+    return out
+
+
+def quantize_u8(values: np.ndarray, scale: float, offset: float) -> np.ndarray:
+    """float32 array -> uint8 codes clamp(rint(fma(v, scale, offset)), 0, 255), same shape."""
+    a = np.ascontiguousarray(values, dtype=np.float32)
+    out = np.empty(a.shape, dtype=np.uint8)
+    _load().harris_ref_quantize_u8(_ptr(a), a.size, scale, offset, _ptr(out))
     return out

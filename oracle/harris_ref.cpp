@@ -319,6 +319,18 @@ void harris_ref_round_bfloat16(const float* in, long long count, uint16_t* out) 
     for (long long i = 0; i < count; ++i) out[i] = round_to_16bit(in[i], 8, -126, 8);
 }
 
+// 8-bit result codes of the library's quantised result option (not part of the thesis):
+// code = clamp(round_to_nearest_even(fma(v, scale, offset)), 0, 255), the multiply-add rounded
+// once in float32 (std::fmaf is the exact fused operation), NaN -> 0.
+void harris_ref_quantize_u8(const float* in, long long count, float scale, float offset, uint8_t* out) {
+    for (long long i = 0; i < count; ++i) {
+        const float t = std::fmaf(in[i], scale, offset);
+        if (std::isnan(t)) { out[i] = 0; continue; }
+        const float r = std::nearbyintf(t);                  // default rounding mode: ties to even
+        out[i] = (uint8_t)(r <= 0.0f ? 0.0f : r >= 255.0f ? 255.0f : r);
+    }
+}
+
 int harris_ref_hardware_threads(void) { return (int)std::max(1u, std::thread::hardware_concurrency()); }
 
 }  // extern "C"

@@ -21,9 +21,9 @@ _LIB_PATH = os.path.join(_HERE, "libharris.so")
 
 #: every symbol include/harris.h declares
 EXPORTS = ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan", "harris_plan_typed",
-           "harris_coarsity_pitched", "harris_coarsity_typed", "harris_coarsity_grouped",
+           "harris_coarsity_pitched", "harris_coarsity_typed", "harris_coarsity_quantized", "harris_coarsity_grouped",
            "harris_grouped_workspace_bytes", "harris_probe_copy", "harris_strerror", "harris_version")
-HARRIS_OUT_F32, HARRIS_OUT_F16, HARRIS_OUT_BF16 = 0, 1, 2
+HARRIS_OUT_F32, HARRIS_OUT_F16, HARRIS_OUT_BF16, HARRIS_OUT_U8 = 0, 1, 2, 3
 
 
 class HarrisError(RuntimeError):
@@ -78,6 +78,8 @@ def load_library() -> ctypes.CDLL:
     lib.harris_coarsity_pitched.restype = ci
     lib.harris_coarsity_typed.argtypes = [vp, ci, ci, ci, ci, ctypes.POINTER(HarrisLayout), cf, cf, ci, vp, ci, tp, vp]
     lib.harris_coarsity_typed.restype = ci
+    lib.harris_coarsity_quantized.argtypes = [vp, ci, ci, ci, ci, ctypes.POINTER(HarrisLayout), cf, cf, ci, cf, cf, vp, tp, vp]
+    lib.harris_coarsity_quantized.restype = ci
     lib.harris_plan_typed.argtypes = [ci, ci, ci, ci, ci, ci, ci, tp, tp, ctypes.POINTER(ctypes.c_longlong)]
     lib.harris_plan_typed.restype = ci
     lib.harris_coarsity_grouped.argtypes = [vp, ci, ci, ci, ci, cf, cf, ci, ci, vp, ctypes.c_longlong, vp, vp]
@@ -225,6 +227,31 @@ def harris_coarsity_typed(rgb, out, k: float = 0.04, sobel_scale: float = 1.0, w
         _check(load_library().harris_coarsity_typed(rgb.data_ptr(), dtype, B, H, W, ctypes.byref(lay), k, sobel_scale, window,
                                                     out.data_ptr(), kinds[out.dtype], _tuning_arg(tuning),
                                                     _stream_ptr(stream, rgb.device)))
+    return out
+
+
+def harris_coarsity_quantized(rgb, out, q_scale: float, q_offset: float, k: float = 0.04, sobel_scale: float = 1.0,
+                              window: int = HARRIS_WINDOW_BOX, tuning=None, stream=None):
+    """8-bit result: out (uint8 [batch][H-4][W-4], may be a view) = clamp(rint(fma(v, q_scale, q_offset)), 0, 255)."""
+    import torch
+    if (not isinstance(rgb, torch.Tensor) or rgb.device.type != "cuda" or rgb.dtype not in (torch.float32, torch.uint8)
+            or rgb.dim() != 4 or rgb.shape[1] != 3):
+        raise TypeError("rgb must be a float32 or uint8 ROCm tensor of shape [batch][3][H][W]")
+    B, _, H, W = rgb.shape
+    if H < 4 or W < 4:
+        raise HarrisError(-2, harris_strerror(-2))
+    if (not isinstance(out, torch.Tensor) or out.device != rgb.device or out.dtype != torch.uint8
+            or tuple(out.shape) != (B, H - 4, W - 4)):
+        raise ValueError("out must be a uint8 tensor [batch][H-4][W-4] on rgb's device")
+    if (W > 1 and rgb.stride(3) != 1) or (W - 4 > 1 and out.stride(2) != 1):
+        raise ValueError("the last dimension of rgb and out must have stride 1")
+    lay = HarrisLayout(rgb.stride(2) if H > 1 else W, rgb.stride(1), rgb.stride(0) if B > 1 else 3 * rgb.stride(1),
+                       out.stride(1) if H - 4 > 1 else max(W - 4, 1), out.stride(0) if B > 1 else max(1, (H - 4) * out.stride(1)))
+    dtype = HARRIS_U8 if rgb.dtype == torch.uint8 else HARRIS_F32
+    with torch.cuda.device(rgb.device):
+        _check(load_library().harris_coarsity_quantized(rgb.data_ptr(), dtype, B, H, W, ctypes.byref(lay), k, sobel_scale, window,
+                                                        q_scale, q_offset, out.data_ptr(), _tuning_arg(tuning),
+                                                        _stream_ptr(stream, rgb.device)))
     return out
 
 

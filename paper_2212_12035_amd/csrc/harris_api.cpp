@@ -14,7 +14,8 @@ constexpr int kVersion = 300;   // 0.3.0
 bool power_of_two_aligned(uintptr_t p, unsigned bytes) { return (p & (uintptr_t)(bytes - 1)) == 0; }
 
 int elem_size(int dtype) { return dtype == HARRIS_U8 ? 1 : 4; }
-int out_elem_size(int out_dtype) { return out_dtype == HARRIS_OUT_F32 ? 4 : 2; }
+int out_elem_size(int out_dtype) { return out_dtype == HARRIS_OUT_F32 ? 4 : out_dtype == HARRIS_OUT_U8 ? 1 : 2; }
+bool known_out_dtype(int d) { return d == HARRIS_OUT_F32 || d == HARRIS_OUT_F16 || d == HARRIS_OUT_BF16 || d == HARRIS_OUT_U8; }
 
 // Can every lane load px input elements and store its result columns with single
 // vector accesses?  Loads are px*elem bytes wide up to 16; stores are min(px,4) result elements.
@@ -29,7 +30,7 @@ bool px_fits(int px, int dtype, int out_dtype, int W, int rgb_align, int out_ali
 int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int out_align, const harris_tuning* tuning,
          harris_tuning* chosen, long long* n_blocks, harris_launch::Params* params) {
     if (dtype != HARRIS_F32 && dtype != HARRIS_U8) return HARRIS_ERR_ARG;
-    if (out_dtype != HARRIS_OUT_F32 && out_dtype != HARRIS_OUT_F16 && out_dtype != HARRIS_OUT_BF16) return HARRIS_ERR_ARG;
+    if (!known_out_dtype(out_dtype)) return HARRIS_ERR_ARG;
     if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
     if (W > (1 << 28)) return HARRIS_ERR_SHAPE;      // byte offsets within a row are 32-bit
     if (rgb_align < 1 || out_align < out_elem_size(out_dtype)) return HARRIS_ERR_ARG;
@@ -53,19 +54,19 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     if (t.rows < 0 || t.prefetch < 0 || t.waves_per_block < 0) return HARRIS_ERR_ARG;
     // px = 8 and a prefetch depth exist only in the band schedule.
     if (t.schedule == 0) t.schedule = t.px <= 4 && t.prefetch == 0 ? HARRIS_SCHEDULE_TILES : HARRIS_SCHEDULE_BANDS;
-    if (out_dtype != HARRIS_OUT_F32 && t.schedule != HARRIS_SCHEDULE_TILES) return HARRIS_ERR_ARG;   // 16-bit results: tile kernel only
+    if (out_dtype != HARRIS_OUT_F32 && t.schedule != HARRIS_SCHEDULE_TILES) return HARRIS_ERR_ARG;   // 16- and 8-bit results: tile kernel only
     // Strip borders on 64-byte boundaries of the result rows: the tile kernel with 16-byte lanes.
     const bool can_align = t.schedule == HARRIS_SCHEDULE_TILES && t.px == 4;
     if ((t.flags & (HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_KEEP_SHARED_ROWS)) && !can_align) return HARRIS_ERR_ARG;
     // Measured, moved against fixed borders: 378 against 393 us on 64x1080x1920 float32, 12.5
     // against 12.8 us on 1536x2560, 37.0 against 37.3 us on 2832x4256, 89 against 93 us on
     // 8192x8192 uint8.
-    // 16-bit results pay more for moved borders (strips of 224 instead of 252 columns): worth it
-    // only for large float32 inputs (64x1080x1920: 341 against 359 us; 1536x2560: 12.8 against
+    // 16-bit results pay more for moved borders (strips of 224 instead of 252 columns; 192 for
+    // 8-bit results, which never get them by default): worth it only for large float32 inputs (64x1080x1920: 341 against 359 us; 1536x2560: 12.8 against
     // 12.4 us; 8192x8192 uint8: 81 against 74 us).
     if (!(t.flags & (HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_PLAIN_STORES))) {
         const long long bytes = (long long)batch * (3LL * H * W * elem_size(dtype) + (long long)out_elem_size(out_dtype) * n * m);
-        const bool align = can_align && (out_dtype == HARRIS_OUT_F32 || (dtype == HARRIS_F32 && bytes > (128LL << 20)));
+        const bool align = can_align && (out_dtype == HARRIS_OUT_F32 || (out_dtype != HARRIS_OUT_U8 && dtype == HARRIS_F32 && bytes > (128LL << 20)));
         t.flags |= align ? HARRIS_TUNE_ALIGNED_STORES : HARRIS_TUNE_PLAIN_STORES;
     }
     // As few strips as 64-lane wavefronts allow, all of the same width.  A moved border lies up
@@ -202,11 +203,17 @@ int harris_plan_typed(int dtype, int out_dtype, int batch, int H, int W, int rgb
     return plan(dtype, out_dtype, batch, H, W, rgb_align, out_align, tuning, chosen, n_blocks, nullptr);
 }
 
-int harris_coarsity_typed(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
-                          float k, float sobel_scale, int window, void* out, int out_dtype,
-                          const harris_tuning* tuning, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// Every entry point of the fused kernel ends here.
+int run(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
+        float k, float sobel_scale, int window, void* out, int out_dtype, float q_scale, float q_offset,
+        const harris_tuning* tuning, void* stream) {
     if (dtype != HARRIS_F32 && dtype != HARRIS_U8) return HARRIS_ERR_ARG;
-    if (out_dtype != HARRIS_OUT_F32 && out_dtype != HARRIS_OUT_F16 && out_dtype != HARRIS_OUT_BF16) return HARRIS_ERR_ARG;
+    if (!known_out_dtype(out_dtype)) return HARRIS_ERR_ARG;
+    if (!isfinite(q_scale) || !isfinite(q_offset)) return HARRIS_ERR_ARG;
     if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
     if (!isfinite(k) || !isfinite(sobel_scale)) return HARRIS_ERR_ARG;
     if (window != HARRIS_WINDOW_BOX && window != HARRIS_WINDOW_BINOMIAL) return HARRIS_ERR_ARG;
@@ -265,7 +272,26 @@ int harris_coarsity_typed(const void* rgb, int dtype, int batch, int H, int W, c
     p.wb = 0.114f * in_scale;
     p.k = k;
     p.binomial = window == HARRIS_WINDOW_BINOMIAL ? 1 : 0;
+    p.q_scale = q_scale;
+    p.q_offset = q_offset;
     return harris_launch::launch(p, shape, n_blocks, dtype, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+int harris_coarsity_typed(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
+                          float k, float sobel_scale, int window, void* out, int out_dtype,
+                          const harris_tuning* tuning, void* stream) {
+    if (out_dtype == HARRIS_OUT_U8) return HARRIS_ERR_ARG;          // needs a scale: harris_coarsity_quantized
+    return run(rgb, dtype, batch, H, W, layout, k, sobel_scale, window, out, out_dtype, 1.0f, 0.0f, tuning, stream);
+}
+
+int harris_coarsity_quantized(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
+                              float k, float sobel_scale, int window, float q_scale, float q_offset,
+                              uint8_t* out, const harris_tuning* tuning, void* stream) {
+    return run(rgb, dtype, batch, H, W, layout, k, sobel_scale, window, out, HARRIS_OUT_U8, q_scale, q_offset, tuning, stream);
 }
 
 int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,

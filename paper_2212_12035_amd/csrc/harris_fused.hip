@@ -188,6 +188,24 @@ __device__ __forceinline__ void store_row_16(const float (&o)[PX], __amdgpu_buff
     }
 }
 
+// PX results of one lane as 8-bit codes clamp(rint(fma(v, scale, offset)), 0, 255); NaN gives 0
+// (the maximum of NaN and 0 is 0).  voff is the lane's byte offset in the row (1 byte per column).
+template <int PX>
+__device__ __forceinline__ void store_row_8(const float (&o)[PX], float scale, float offset, __amdgpu_buffer_rsrc_t rs, uint32_t voff) {
+    uint32_t c[PX];
+#pragma unroll
+    for (int i = 0; i < PX; ++i) c[i] = (uint32_t)fminf(fmaxf(rintf(fmaf(o[i], scale, offset)), 0.0f), 255.0f);
+    if constexpr (PX >= 4) {
+#pragma unroll
+        for (int j = 0; j < PX / 4; ++j)
+            __builtin_amdgcn_raw_buffer_store_b32(c[4 * j] | (c[4 * j + 1] << 8) | (c[4 * j + 2] << 16) | (c[4 * j + 3] << 24), rs, voff + 4 * j, 0, HARRIS_STORE_AUX);
+    } else if constexpr (PX == 2) {
+        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(c[0] | (c[1] << 8)), rs, voff, 0, HARRIS_STORE_AUX);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)c[0], rs, voff, 0, HARRIS_STORE_AUX);
+    }
+}
+
 // Stage a0 + a1: element i of plane c as float (8-bit values are converted; their
 // 1/255 is folded into the gray weights), then gray = wr*R + wg*G + wb*B.
 template <typename In, int PX>
@@ -438,12 +456,12 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 
     const unsigned col = (unsigned)strip * p.strip_pitch + lane * PX;
     const unsigned lcol = min(col, (unsigned)(p.W - PX));
-    // Results are float32 or 16-bit: esh is log2 of a result element's bytes.
-    const unsigned esh = p.out_kind == HARRIS_OUT_F32 ? 2u : 1u;
+    // Results are float32, 16-bit or 8-bit: esh is log2 of a result element's bytes.
+    const unsigned esh = p.out_kind == HARRIS_OUT_F32 ? 2u : p.out_kind == HARRIS_OUT_U8 ? 0u : 1u;
     // With aligned stores the border between this strip and the next lies, in each result row,
     // on the first 64-byte boundary of that row's address at or after the nominal border: up to
-    // 12 (float32) or 28 (16-bit) columns further right.  border_mask is the number of columns
-    // per 64 bytes, minus one (15 or 31), or 0.
+    // 12 (float32), 28 (16-bit) or 60 (8-bit) columns further right.  border_mask is the number
+    // of columns per 64 bytes, minus one (15, 31 or 63), or 0.
     const unsigned border_mask = (p.flags & HARRIS_TUNE_ALIGNED_STORES) ? (64u >> esh) - 1u : 0u;
     const unsigned x0 = (unsigned)strip * p.strip_pitch;        // first result column of this strip
     // Lanes beyond the strip's columns, the border's reach and the 4-column halo request nothing
@@ -553,10 +571,15 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
             constexpr int j = decltype(jj)::value;
             if (j < RW - 4 || wave + 1 < n_waves) store_row_16<PX, false>(results[j], out_rs[j], lane_bytes + out_lead[j]);
         });
-    } else {
+    } else if (p.out_kind == HARRIS_OUT_BF16) {
         static_for<0, RW>([&](auto jj) {
             constexpr int j = decltype(jj)::value;
             if (j < RW - 4 || wave + 1 < n_waves) store_row_16<PX, true>(results[j], out_rs[j], lane_bytes + out_lead[j]);
+        });
+    } else {
+        static_for<0, RW>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+            if (j < RW - 4 || wave + 1 < n_waves) store_row_8<PX>(results[j], p.q_scale, p.q_offset, out_rs[j], lane_bytes + out_lead[j]);
         });
     }
 }

@@ -62,7 +62,8 @@ struct Params {
     float wr, wg, wb;       // gray weights, times the Sobel scale (and 1/255 for 8-bit input)
     float k;                // coarsity constant
     unsigned flags;         // HARRIS_TUNE_* bits
-    unsigned out_kind;      // a harris_out_dtype (16-bit results: tile kernel only)
+    unsigned out_kind;      // a harris_out_dtype (other than float32: tile kernel only)
+    float q_scale, q_offset;   // 8-bit results: code = clamp(rint(fma(v, q_scale, q_offset)), 0, 255)
     int binomial;           // 1: window [1 2 1; 2 4 2; 1 2 1], 0: unweighted 3x3 sum
     unsigned n_bands;       // bands (BANDS) or tiles down the image (TILES)
     unsigned blocks_x;      // BANDS: workgroups across a row of bands

@@ -142,14 +142,24 @@ def test_plan_for_16_bit_results(pkg):
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, BF16, 1, 64, 96, out_align=4)[0]["px"] == 2
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, BF16, 1, 64, 96, out_align=2)[0]["px"] == 1
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_F32, 1, 1536, 2560) == pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
-    for bad in (dict(out_dtype=3), dict(out_dtype=F16, tuning=dict(schedule=1)), dict(out_dtype=F16, tuning=dict(prefetch=3)),
+    for bad in (dict(out_dtype=4), dict(out_dtype=F16, tuning=dict(schedule=1)), dict(out_dtype=F16, tuning=dict(prefetch=3)),
                 dict(out_dtype=F16, out_align=1), dict(out_dtype=F16, tuning=dict(px=8))):
         with pytest.raises(pkg.HarrisError) as e:
             pkg.harris_plan_typed(pkg.HARRIS_F32, bad["out_dtype"], 1, 64, 96, out_align=bad.get("out_align", 16), tuning=bad.get("tuning"))
         assert e.value.status == -3
+    # 8-bit results: plain strips by default, at most 192 columns with moved borders, byte-aligned rows allowed
+    u8out, blocks = pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_U8, 64, 1080, 1920)
+    assert u8out["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES and blocks == 64 * 90 * 8
+    assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_U8, 64, 1080, 1920, tuning=dict(flags=pkg.HARRIS_TUNE_ALIGNED_STORES))[1] == 64 * 90 * 10
+    assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_U8, 1, 64, 96, out_align=1)[0]["px"] == 1
     lib = pkg.load_library()
     one = ctypes.c_void_p(4096)
     assert lib.harris_coarsity_typed(one, 0, 1, 64, 64, None, 0.04, 1.0, 0, one, 7, None, None) == -3
+    assert lib.harris_coarsity_typed(one, 0, 1, 64, 64, None, 0.04, 1.0, 0, one, pkg.HARRIS_OUT_U8, None, None) == -3   # 8-bit codes need a scale
+    assert lib.harris_coarsity_quantized(one, 0, 1, 64, 64, None, 0.04, 1.0, 0, float("nan"), 0.0, one, None, None) == -3
+    assert lib.harris_coarsity_quantized(one, 0, 1, 64, 64, None, 0.04, 1.0, 0, 1.0, float("inf"), one, None, None) == -3
+    assert lib.harris_coarsity_quantized(None, 0, 1, 64, 64, None, 0.04, 1.0, 0, 1.0, 0.0, one, None, None) == -1
+    assert lib.harris_coarsity_quantized(None, 0, 0, 64, 64, None, 0.04, 1.0, 0, 1.0, 0.0, None, None, None) == 0
     assert lib.harris_coarsity_typed(one, 0, 1, 64, 64, None, 0.04, 1.0, 0, ctypes.c_void_p(4097), 1, None, None) == -3
     assert lib.harris_coarsity_typed(None, 0, 0, 64, 64, None, 0.04, 1.0, 0, None, 2, None, None) == 0
 

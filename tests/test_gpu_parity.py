@@ -408,6 +408,40 @@ def test_16_bit_results_layouts_and_overflow(gpu, oracle):
     assert e.value.status == -3
 
 
+def test_8_bit_codes(gpu, oracle):
+    # (1) The codes equal the oracle's quantisation of the kernel's own float32 result bit for
+    # bit.  (2) Against the oracle's codes of the oracle's float32 result: two float32 values
+    # within the bar give codes at most ceil(bar * |scale|) + 1 apart.  Several lane widths,
+    # tile shapes, padded rows, every phase of the row address, guard bands, clamping at both ends.
+    import torch
+    for rgb, scale, q_scale, q_offset in ((hi.rectangles_f32(81, 2, 45, 520), 1.0, 0.5, 128.0), (hi.white_noise_u8(82, 1, 33, 264), 1.0, 2.0, 100.0),
+                                          (hi.white_noise_f32(83, 1, 37, 98), 1.0, -1.0, 64.0), (hi.white_noise_f32(84, 2, 22, 131), S12, 30000.0, 10.0)):
+        B, _, H, W = rgb.shape
+        n, m = H - 4, W - 4
+        want32 = oracle.harris(rgb, K, scale)
+        want8 = oracle.quantize_u8(want32, q_scale, q_offset).astype(int)
+        src = torch.from_numpy(rgb).cuda()
+        slack = int(np.ceil((1e-4 * float(np.abs(want32).max()) + 1e-6) * abs(q_scale))) + 1
+        for pitch, off, tune in ((m, 0, None), (m + 4, 4, dict(schedule=2, rows=8, waves_per_block=3)), (m + 9, 1, None),
+                                 (m, 8, dict(flags=gpu.HARRIS_TUNE_ALIGNED_STORES) if W % 4 == 0 else None)):
+            say("case 8-bit codes %s %s pitch=%d offset=%d tuning %s" % (rgb.dtype, rgb.shape, pitch, off, tune))
+            flat = torch.full((B * n * pitch + 32,), 77, dtype=torch.uint8, device="cuda")
+            view = flat[off:off + B * n * pitch].view(B, n, pitch)[:, :, :m]
+            gpu.harris_coarsity_quantized(src, view, q_scale, q_offset, K, scale, tuning=tune)
+            f32 = torch.empty((B, n, m), device="cuda")
+            gpu.harris_coarsity_typed(src, f32, K, scale)
+            torch.cuda.synchronize()
+            got = view.cpu().numpy()
+            assert np.array_equal(got, oracle.quantize_u8(f32.cpu().numpy(), q_scale, q_offset))
+            assert np.all(np.abs(got.astype(int) - want8) <= slack)
+            assert got.min() == 0 or got.max() == 255 or q_scale == 0.5       # the chosen scales reach the clamp
+            rest = flat.clone()
+            rest[off:off + B * n * pitch].view(B, n, pitch)[:, :, :m] = 77
+            assert bool((rest == 77).all())
+    with pytest.raises(gpu.HarrisError):
+        gpu.harris_coarsity_quantized(src, view, 1.0, 0.0, tuning=dict(schedule=1))
+
+
 # ---------------------------------------------------------------- seeded random shapes, layouts and launch shapes
 
 def test_random_shapes_layouts_and_launch_shapes(gpu, oracle):

@@ -388,6 +388,29 @@ def test_rounding_to_binary16_and_bfloat16(oracle):
     assert (int(bf16(nan)[0]) & 0x7f80) == 0x7f80 and (int(bf16(nan)[0]) & 0x007f) != 0
 
 
+def test_quantisation_to_8_bit_codes(oracle):
+    # Exact cases: v * scale + offset is representable, so the code is fixed by the definition:
+    # ties go to the even integer, the range is clamped, NaN gives 0.
+    q = lambda v, s, o: oracle.quantize_u8(np.array(v, dtype=np.float32), s, o).tolist()
+    assert q([0.0, 0.25, 0.5, 0.75, 1.0, 1.25, 1.5, 2.5, 3.5, 254.5, 255.5, 300.0, -0.5, -3.0], 1.0, 0.0) == [0, 0, 0, 1, 1, 1, 2, 2, 4, 254, 255, 255, 0, 0]
+    assert q([0.0, 1.0, -1.0, 63.75, -64.0, 1e30, -1e30], 2.0, 128.0) == [128, 130, 126, 255, 0, 255, 0]
+    assert q([float("nan"), float("inf"), float("-inf")], 1.0, 0.0) == [0, 255, 0]
+    # random values against the same formula in float64 (exact product, one rounding of the sum):
+    # equal except where the sum lies within 1e-4 of a rounding border
+    rng = np.random.default_rng(3)
+    v = (rng.standard_normal(200000) * 60).astype(np.float32)
+    for s, o in ((1.0, 128.0), (0.37, 17.5), (-2.0, 100.0)):
+        t = v.astype(np.float64) * np.float64(np.float32(s)) + np.float64(np.float32(o))
+        want = np.clip(np.rint(t), 0, 255).astype(np.uint8)
+        got = oracle.quantize_u8(v, s, o)
+        near_border = np.abs(t - np.floor(t) - 0.5) < 1e-4
+        assert np.array_equal(got[~near_border], want[~near_border]) and np.all(np.abs(got.astype(int) - want.astype(int)) <= 1)
+    # the multiply-add is rounded once: 4097 * 4097 = 16785409 is not a float32 (it would round to
+    # 16785408), so with offset -16785400 the fused result is 9 and a separately rounded one 8
+    assert float(np.float32(-16785400.0)) == -16785400.0
+    assert oracle.quantize_u8(np.array([4097.0], dtype=np.float32), 4097.0, -16785400.0)[0] == 9
+
+
 # ---------------------------------------------------------------- input generators (host logic)
 
 def test_generators_are_deterministic_and_in_range():
