@@ -77,23 +77,9 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     const long long n_strips = m > 0 ? (m + max_pitch - 1) / max_pitch : 0;
     const long long pitch = n_strips > 0 ? ((m + n_strips - 1) / n_strips + t.px - 1) / t.px * t.px : max_pitch;
 
-    // Bytes the launch moves.  Measured rule for the load policy of float32 input: up to about half
-    // the 256 MB last-level cache everything is loaded non-temporal; up to about 400 MB non-temporal
-    // except the rows two tiles share, which the default policy keeps in L2 for the second reader
-    // (2832x4256: 34.6 us against 37.1 us all-default and 39.7 us all-non-temporal; 4096x4096:
-    // 49.7 / 53.8 / 54.6 us); beyond that everything with the default policy (64x1080x1920: 379 us
-    // against 380 us mixed and 404 us non-temporal; 8192x8192: 181 / 188 / 214 us).  8-bit input:
-    // non-temporal with the shared rows kept at every size (8192x8192: 91.1 us against 91.8 us
-    // non-temporal and 105 us default; 64x1080x1920: 176 / 181 / 176 us).
+    // Bytes the launch moves.
     const long long elem = elem_size(dtype);
     const long long footprint = (long long)batch * (3LL * H * W * elem + (long long)out_elem_size(out_dtype) * n * m);
-    if (!(t.flags & (HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS))) {
-        if (dtype == HARRIS_F32 && footprint > (400LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
-        else if (dtype == HARRIS_F32 && footprint > (128LL << 20) && can_align) t.flags |= HARRIS_TUNE_STREAM_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS;
-        else if (dtype == HARRIS_F32 && footprint > (128LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
-        else if (dtype == HARRIS_U8 && can_align) t.flags |= HARRIS_TUNE_STREAM_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS;
-        else t.flags |= HARRIS_TUNE_STREAM_LOADS;
-    }
 
     // Default tile shape.  A problem that one pass over the 256 CUs can hold is fastest as one
     // tile per CU: all CUs then carry the same load and finish together (measured on
@@ -153,6 +139,22 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     const long long n_bands = n > 0 ? ((long long)n + tile_rows - 1) / tile_rows : 0;
     const long long tiles_per_image = n_bands * n_strips;
     const long long n_tiles = tiles_per_image * batch;
+
+    // Load policy, measured.  One tile per CU (at most 256 tiles): everything non-temporal (1536x2560:
+    // 12.2 us against 12.6 us with the shared rows kept).  Many tiles, float32 up to about 400 MB and
+    // 8-bit input: non-temporal except the rows two tiles share, which the default policy keeps in L2
+    // for the second reader (2832x4256: 34.6 us against 37.1 us all-default and 39.7 us
+    // all-non-temporal; 4096x4096: 49.7 / 53.8 / 54.6 us; 32x512x512: 25.7 / 27.0 / 26.8 us; 8192x8192
+    // uint8: 91.1 / 105 / 91.8 us).  Larger float32 problems: everything with the default policy
+    // (64x1080x1920: 379 us against 380 us mixed and 404 us non-temporal; 8192x8192: 181 / 188 / 214 us).
+    // Bands and lanes narrower than 16 bytes have no mixed policy: default-policy loads from 128 MB on.
+    if (!(t.flags & (HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS))) {
+        const bool one_tile_per_cu = t.schedule == HARRIS_SCHEDULE_TILES && n_tiles <= 256;
+        if (dtype == HARRIS_F32 && footprint > (400LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
+        else if (can_align && !one_tile_per_cu) t.flags |= HARRIS_TUNE_STREAM_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS;
+        else if (dtype == HARRIS_F32 && footprint > (128LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
+        else t.flags |= HARRIS_TUNE_STREAM_LOADS;
+    }
     // TILES: one workgroup per tile.  BANDS: one wavefront per band of a strip; a workgroup
     // of 2 or 4 wavefronts takes 2 bands x 1 or 2 strips.
     const long long group_h = t.waves_per_block >= 2 ? 2 : 1, group_w = t.waves_per_block / group_h;

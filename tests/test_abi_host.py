@@ -87,6 +87,10 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     big, blocks = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920)
     assert (big["rows"], big["waves_per_block"]) == (4, 4) and blocks == 64 * 90 * 8
     assert big["flags"] == pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES
+    # many tiles below 128 MB as well (32 images of 512x512 cannot be one tile per CU): shared rows kept
+    many, blocks = pkg.harris_plan(pkg.HARRIS_F32, 32, 512, 512)
+    assert (many["rows"], many["waves_per_block"]) == (4, 4) and blocks > 256
+    assert many["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_ALIGNED_STORES
     # lanes narrower than 16 bytes have no mixed policy: default-policy loads from 128 MB on
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4258)[0]["flags"] == pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES
     # 8-bit input: non-temporal loads; 35 strips of at most 240 columns cover 8188
