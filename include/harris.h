@@ -43,7 +43,7 @@ extern "C" {
 typedef enum harris_status {
     HARRIS_OK = 0,
     HARRIS_ERR_NULL = -1,    /* rgb or out is NULL although the result is not empty        */
-    HARRIS_ERR_SHAPE = -2,   /* batch < 0, H < 4, W < 4, W > 2^28, more than 2^31-1 tiles, or
+    HARRIS_ERR_SHAPE = -2,   /* batch < 0, H < 4, W < 4, W > 2^28, H > 2^30, more than 2^31-1 tiles, or
                                 pitches smaller than the image                               */
     HARRIS_ERR_ARG = -3,     /* k or sobel_scale not finite, unknown dtype/window/tuning,
                                 misaligned pointer                                          */

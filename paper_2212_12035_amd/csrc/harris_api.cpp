@@ -33,6 +33,7 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     if (!known_out_dtype(out_dtype)) return HARRIS_ERR_ARG;
     if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
     if (W > (1 << 28)) return HARRIS_ERR_SHAPE;      // byte offsets within a row are 32-bit
+    if (H > (1 << 30)) return HARRIS_ERR_SHAPE;      // row indices plus a tile's height stay within int
     if (rgb_align < 1 || out_align < out_elem_size(out_dtype)) return HARRIS_ERR_ARG;
     harris_tuning t = {0, 0, 0, 0, 0, 0u};
     if (tuning) t = *tuning;

@@ -117,6 +117,7 @@ def test_plan_rejects_bad_arguments(pkg):
         ((0, -1, 64, 64), -2), ((0, 1, 3, 64), -2), ((0, 1, 64, 3), -2),
         ((0, 2 ** 31 - 1, 4096, 4096), -2),         # more tiles than a grid can hold
         ((0, 1, 8, 2 ** 28 + 4), -2),               # row offsets would not fit 32 bits
+        ((0, 1, 2 ** 30 + 1, 8), -2),               # row indices would not fit int
     ]:
         with pytest.raises(E) as e:
             pkg.harris_plan(*args)
