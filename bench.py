@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files without comments, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "f180397e8fc9df72484f83761ef90886312d6a39cd18c546f8f8fd55318ab3c3"
-TRAFFIC_BYTES = {"noise_f32_1536x2560": 65262676, "rects_f32_64x1080x1920": 2194572007,
-                 "blobs_f32_2832x4256": 199700018, "noise_u8_8192x8192": 489675781}
+TRAFFIC_SOURCES_SHA256 = "2a9b0286016c408394ae5567649919a857b09b35700884ee9a59537a3fe0d1b2"
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 65242621, "rects_f32_64x1080x1920": 2195205233,
+                 "blobs_f32_2832x4256": 199708236, "noise_u8_8192x8192": 489744018}
 
 
 def kernel_sources_sha256():
