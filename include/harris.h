@@ -106,6 +106,10 @@ typedef struct harris_tuning {
                                         that two vertically adjacent tiles both read (the first and the
                                         last four of a tile) are loaded with the default policy instead,
                                         so that the second reader finds them in L2                   */
+#define HARRIS_TUNE_FLAG_HANDOFF 128u /* TILES with px = 4 and plain non-temporal loads only: a wavefront
+                                        waits for a ready flag of the wavefront below it instead of
+                                        the workgroup's barrier (and a barrier holds the stores back
+                                        until the workgroup's loads are in): for few, large tiles     */
 #define HARRIS_TUNE_ALIGNED_STORES 16u /* TILES with px = 4 only: in every result row the border between
                                         two strips is moved right to the next 64-byte boundary of the
                                         row's address, so that no 64-byte block of the result is

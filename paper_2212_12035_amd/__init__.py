@@ -7,7 +7,7 @@ memory and streams.
 from .binding import (  # noqa: F401
     HARRIS_F32, HARRIS_U8, HARRIS_WINDOW_BOX, HARRIS_WINDOW_BINOMIAL,
     HARRIS_SCHEDULE_BANDS, HARRIS_SCHEDULE_TILES, HARRIS_TUNE_NO_ALTERNATE, HARRIS_TUNE_NO_XCD_REMAP,
-    HARRIS_TUNE_CACHED_LOADS, HARRIS_TUNE_STREAM_LOADS, HARRIS_TUNE_ALIGNED_STORES, HARRIS_TUNE_PLAIN_STORES, HARRIS_TUNE_KEEP_SHARED_ROWS,
+    HARRIS_TUNE_CACHED_LOADS, HARRIS_TUNE_STREAM_LOADS, HARRIS_TUNE_ALIGNED_STORES, HARRIS_TUNE_PLAIN_STORES, HARRIS_TUNE_KEEP_SHARED_ROWS, HARRIS_TUNE_FLAG_HANDOFF,
     HARRIS_OUT_F32, HARRIS_OUT_F16, HARRIS_OUT_BF16, HARRIS_OUT_U8, harris_coarsity_typed, harris_coarsity_quantized,
     harris_plan_typed,
     HarrisError, HarrisTuning, HarrisLayout, library_path, load_library, harris_coarsity_pitched,

@@ -14,7 +14,7 @@ HARRIS_F32, HARRIS_U8 = 0, 1
 HARRIS_WINDOW_BOX, HARRIS_WINDOW_BINOMIAL = 0, 1
 HARRIS_SCHEDULE_BANDS, HARRIS_SCHEDULE_TILES = 1, 2
 HARRIS_TUNE_NO_ALTERNATE, HARRIS_TUNE_NO_XCD_REMAP, HARRIS_TUNE_CACHED_LOADS, HARRIS_TUNE_STREAM_LOADS = 1, 2, 4, 8
-HARRIS_TUNE_ALIGNED_STORES, HARRIS_TUNE_PLAIN_STORES, HARRIS_TUNE_KEEP_SHARED_ROWS = 16, 32, 64
+HARRIS_TUNE_ALIGNED_STORES, HARRIS_TUNE_PLAIN_STORES, HARRIS_TUNE_KEEP_SHARED_ROWS, HARRIS_TUNE_FLAG_HANDOFF = 16, 32, 64, 128
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libharris.so")

@@ -38,9 +38,10 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     harris_tuning t = {0, 0, 0, 0, 0, 0u};
     if (tuning) t = *tuning;
     if (t.flags & ~(HARRIS_TUNE_NO_ALTERNATE | HARRIS_TUNE_NO_XCD_REMAP | HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS |
-                    HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_PLAIN_STORES | HARRIS_TUNE_KEEP_SHARED_ROWS)) return HARRIS_ERR_ARG;
+                    HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_PLAIN_STORES | HARRIS_TUNE_KEEP_SHARED_ROWS | HARRIS_TUNE_FLAG_HANDOFF)) return HARRIS_ERR_ARG;
     if ((t.flags & HARRIS_TUNE_CACHED_LOADS) && (t.flags & HARRIS_TUNE_STREAM_LOADS)) return HARRIS_ERR_ARG;
     if ((t.flags & HARRIS_TUNE_KEEP_SHARED_ROWS) && !(t.flags & HARRIS_TUNE_STREAM_LOADS)) return HARRIS_ERR_ARG;
+    if ((t.flags & HARRIS_TUNE_FLAG_HANDOFF) && (t.flags & (HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS))) return HARRIS_ERR_ARG;
     if ((t.flags & HARRIS_TUNE_ALIGNED_STORES) && (t.flags & HARRIS_TUNE_PLAIN_STORES)) return HARRIS_ERR_ARG;
     if (t.schedule != 0 && t.schedule != HARRIS_SCHEDULE_BANDS && t.schedule != HARRIS_SCHEDULE_TILES) return HARRIS_ERR_ARG;
 
@@ -58,7 +59,7 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     if (out_dtype != HARRIS_OUT_F32 && t.schedule != HARRIS_SCHEDULE_TILES) return HARRIS_ERR_ARG;   // 16- and 8-bit results: tile kernel only
     // Strip borders on 64-byte boundaries of the result rows: the tile kernel with 16-byte lanes.
     const bool can_align = t.schedule == HARRIS_SCHEDULE_TILES && t.px == 4;
-    if ((t.flags & (HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_KEEP_SHARED_ROWS)) && !can_align) return HARRIS_ERR_ARG;
+    if ((t.flags & (HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_KEEP_SHARED_ROWS | HARRIS_TUNE_FLAG_HANDOFF)) && !can_align) return HARRIS_ERR_ARG;
     // Measured, moved against fixed borders: 378 against 393 us on 64x1080x1920 float32, 12.5
     // against 12.8 us on 1536x2560, 37.0 against 37.3 us on 2832x4256, 89 against 93 us on
     // 8192x8192 uint8.
@@ -149,12 +150,19 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     // uint8: 91.1 / 105 / 91.8 us).  Larger float32 problems: everything with the default policy
     // (64x1080x1920: 379 us against 380 us mixed and 404 us non-temporal; 8192x8192: 181 / 188 / 214 us).
     // Bands and lanes narrower than 16 bytes have no mixed policy: default-policy loads from 128 MB on.
+    const bool one_tile_per_cu = t.schedule == HARRIS_SCHEDULE_TILES && n_tiles <= 256;
     if (!(t.flags & (HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS))) {
-        const bool one_tile_per_cu = t.schedule == HARRIS_SCHEDULE_TILES && n_tiles <= 256;
-        if (dtype == HARRIS_F32 && footprint > (400LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
+        if (t.flags & HARRIS_TUNE_FLAG_HANDOFF) t.flags |= HARRIS_TUNE_STREAM_LOADS;
+        else if (dtype == HARRIS_F32 && footprint > (400LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
         else if (can_align && !one_tile_per_cu) t.flags |= HARRIS_TUNE_STREAM_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS;
         else if (dtype == HARRIS_F32 && footprint > (128LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
         else t.flags |= HARRIS_TUNE_STREAM_LOADS;
+        // Ready flags instead of the barrier where tiles are few and tall and the input float32
+        // (measured: 1536x2560 12.1 against 12.3 us, 2048x2048 12.7 / 13.2, 2x1536x2560 22.6 / 23.3,
+        // 1080x1920 8.4 / 8.4; 720x1280, 3 wavefronts per tile, 6.4 / 6.1; 2048x4096 uint8 18.1 / 15.2).
+        if (one_tile_per_cu && can_align && dtype == HARRIS_F32 && t.waves_per_block >= 5 &&
+            t.flags == (t.flags & ~(HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS)))
+            t.flags |= HARRIS_TUNE_FLAG_HANDOFF;
     }
     // TILES: one workgroup per tile.  BANDS: one wavefront per band of a strip; a workgroup
     // of 2 or 4 wavefronts takes 2 bands x 1 or 2 strips.

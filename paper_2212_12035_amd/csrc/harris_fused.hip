@@ -428,12 +428,28 @@ __device__ __forceinline__ void pin_values(float (&v)[PX]) {
 // its RW+4 gray rows and stores RW result rows (the last wavefront has no neighbour
 // below and stores RW-4).  A tile yields NW*RW-4 result rows; the tile below re-reads
 // four rows.
-template <typename In, int PX, int RW, int LAUX, bool BINOM>
+//
+// HANDOFF selects how a wavefront learns that the rows below its own are in LDS.  false: the
+// workgroup's barrier, after every wavefront has worked through its own rows.  true: a ready
+// flag per wavefront in LDS, set as soon as its first four gray rows are written; a wavefront
+// waits only for the flag of the one below it, and a barrier before the store burst keeps the
+// stores behind the workgroup's loads.  With one large tile per CU the last wavefront's data
+// arrives long after the first's, and without the flags every wavefront's last four rows would
+// wait for it and then be computed by all at once (1536x2560: 12.2 against 12.4 us); with many
+// small tiles the barrier is faster (720x1280: 6.1 against 6.4 us).
+template <typename In, int PX, int RW, int LAUX, bool BINOM, bool HANDOFF>
 __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::Params p) {
     extern __shared__ __align__(16) float halo_lds[];           // [NW][4][64][PX]
+    __shared__ unsigned ready[16];                              // HANDOFF: wavefront w has published its four rows
 
     const unsigned lane = threadIdx.x % kWave;
     const unsigned wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    if constexpr (HANDOFF) {
+        // Every flag is cleared before any wavefront can look at one.  At this point the
+        // wavefronts of a workgroup are a few hundred cycles apart: the barrier costs nothing measurable.
+        if (lane == 0) __hip_atomic_store(&ready[wave], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __syncthreads();
+    }
     const unsigned n_waves = p.waves_per_block;                 // == blockDim.x / 64
     unsigned tile = blockIdx.x;
     // The grid size is read with all other arguments, not in a branch of its own: one wait
@@ -535,6 +551,12 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 #pragma unroll
             for (int i = 0; i < PX; ++i) my_halo[(size_t)t * kWave * PX + i] = gc[i];
         }
+        if constexpr (HANDOFF && t == 3) {
+            // The four rows are in LDS (LDS operations of a wavefront complete in order; the wait
+            // makes that explicit), then the flag.
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (lane == 0) __hip_atomic_store(&ready[wave], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
         if constexpr (t < 4) {
             row_step<(t < 2 ? 0 : 1), t % 3, PX, BINOM>(lb, gc, p.k, none);
         } else {
@@ -546,9 +568,16 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
         __builtin_amdgcn_sched_barrier(0);
     });
 
-    __syncthreads();
+    if constexpr (!HANDOFF) __syncthreads();
 
     if (wave + 1 < n_waves) {
+        if constexpr (HANDOFF) {
+            // Wavefront wave + 1 sets its flag without depending on anybody (every wavefront runs
+            // through the code above unconditionally), so this wait ends.
+            while (__builtin_amdgcn_readfirstlane(__hip_atomic_load(&ready[wave + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) == 0u)
+                __builtin_amdgcn_s_sleep(4);
+            asm volatile("" ::: "memory");                      // the rows are read after the flag, not before
+        }
         const float* below = halo_lds + ((size_t)(wave + 1) * 4 * kWave + lane) * PX;
         static_for<RW, RW + 4>([&](auto tt) {
             constexpr int t = decltype(tt)::value;
@@ -560,6 +589,7 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
     }
 
     // The last wavefront skips the four rows it has no data for.
+    if constexpr (HANDOFF) __syncthreads();                     // stores only after all of the workgroup's loads
     __builtin_amdgcn_sched_barrier(0);
     if (__builtin_expect(p.out_kind == HARRIS_OUT_F32, 1)) {
         static_for<0, RW>([&](auto jj) {
@@ -602,18 +632,24 @@ hipError_t launch_tiles(const harris_launch::Params& p, dim3 grid, dim3 block, h
     const size_t lds = (size_t)(block.x / kWave) * 4 * kWave * PX * sizeof(float);
     const bool cached = p.flags & HARRIS_TUNE_CACHED_LOADS;
     if constexpr (PX == 4) {
+        // Kernels that exist for 16-byte lanes only (the planner asks for them nowhere else).
+        if (p.flags & HARRIS_TUNE_FLAG_HANDOFF) {
+            if (p.binomial) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, true, true>), grid, block, lds, stream, p);
+            else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, false, true>), grid, block, lds, stream, p);
+            return hipGetLastError();
+        }
         if (p.flags & HARRIS_TUNE_KEEP_SHARED_ROWS) {
-            if (p.binomial) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxKeepShared, true>), grid, block, lds, stream, p);
-            else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxKeepShared, false>), grid, block, lds, stream, p);
+            if (p.binomial) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxKeepShared, true, false>), grid, block, lds, stream, p);
+            else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxKeepShared, false, false>), grid, block, lds, stream, p);
             return hipGetLastError();
         }
     }
     if (p.binomial) {
-        if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, true>), grid, block, lds, stream, p);
-        else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, true>), grid, block, lds, stream, p);
+        if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, true, false>), grid, block, lds, stream, p);
+        else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, true, false>), grid, block, lds, stream, p);
     } else {
-        if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, false>), grid, block, lds, stream, p);
-        else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, false>), grid, block, lds, stream, p);
+        if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, false, false>), grid, block, lds, stream, p);
+        else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, false, false>), grid, block, lds, stream, p);
     }
     return hipGetLastError();
 }

@@ -78,7 +78,12 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     small, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
     # one tile per CU: 11 strips x 23 tiles of 9 wavefronts x 8 rows (68 result rows) = 253 workgroups
     assert small["schedule"] == pkg.HARRIS_SCHEDULE_TILES and (small["rows"], small["waves_per_block"]) == (8, 9) and blocks == 253
-    assert small["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES
+    assert small["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES | pkg.HARRIS_TUNE_FLAG_HANDOFF
+    # few, tall tiles take ready flags instead of the barrier; tiles of fewer than 5 wavefronts keep the barrier
+    assert not pkg.harris_plan(pkg.HARRIS_F32, 1, 720, 1280)[0]["flags"] & pkg.HARRIS_TUNE_FLAG_HANDOFF
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1080, 1920)[0]["flags"] & pkg.HARRIS_TUNE_FLAG_HANDOFF
+    assert not pkg.harris_plan(pkg.HARRIS_U8, 1, 2048, 4096)[0]["flags"] & pkg.HARRIS_TUNE_FLAG_HANDOFF     # 8-bit input keeps the barrier
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=dict(flags=pkg.HARRIS_TUNE_STREAM_LOADS))[0]["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES
     # beyond one tile per CU: many tiles of 4 wavefronts x 4 rows (12 result rows); cached loads for large float32
     mid, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4256)
     assert (mid["schedule"], mid["rows"], mid["waves_per_block"]) == (2, 4, 4) and blocks == 18 * 236
@@ -122,7 +127,8 @@ def test_plan_rejects_bad_arguments(pkg):
         with pytest.raises(E) as e:
             pkg.harris_plan(*args)
         assert e.value.status == status
-    for bad in (dict(px=3), dict(px=4, prefetch=5), dict(schedule=1, px=4, waves_per_block=3), dict(waves_per_block=1), dict(flags=128), dict(flags=12), dict(flags=48), dict(flags=64), dict(flags=64 | 4), dict(schedule=1, flags=64 | 8), dict(px=2, flags=64 | 8), dict(schedule=1, flags=16), dict(px=2, flags=16), dict(rows=-1),
+    for bad in (dict(px=3), dict(px=4, prefetch=5), dict(schedule=1, px=4, waves_per_block=3), dict(waves_per_block=1), dict(flags=256), dict(flags=12), dict(flags=48), dict(flags=64), dict(flags=64 | 4), dict(schedule=1, flags=64 | 8), dict(px=2, flags=64 | 8),
+                dict(flags=128 | 4), dict(flags=128 | 64 | 8), dict(schedule=1, flags=128), dict(px=2, flags=128), dict(schedule=1, flags=16), dict(px=2, flags=16), dict(rows=-1),
                 dict(schedule=3), dict(schedule=2, rows=7), dict(schedule=2, px=2, rows=5), dict(schedule=2, waves_per_block=1), dict(schedule=2, waves_per_block=17),
                 dict(schedule=2, prefetch=3), dict(schedule=2, px=8)):
         with pytest.raises(E) as e:

@@ -163,6 +163,34 @@ def test_tile_schedule_shared_rows_kept_in_cache(gpu, oracle, rows):
                 check(run_gpu(gpu, rgb, k=K, window=window, tuning=tune), want)
 
 
+@pytest.mark.parametrize("rows", [4, 5, 6, 8, 9, 10])
+def test_tile_schedule_ready_flags_instead_of_the_barrier(gpu, oracle, rows):
+    # The hand-off by ready flags has kernel instances of its own: float32 and 8-bit input, both
+    # windows, from 2 to 16 wavefronts per tile, several tiles down the image and a ragged last
+    # one, every result type; plus a workgroup count far above what is resident at once.
+    import torch
+    flags = gpu.HARRIS_TUNE_FLAG_HANDOFF
+    H, W = 151, 4 * 131
+    for rgb in (hi.white_noise_f32(27, 2, H, W), hi.white_noise_u8(28, 2, H, W)):
+        for window in (0, 1):
+            want = oracle.harris(rgb, K, 1.0, window)
+            for waves in (2, 3, 9, 16):
+                tune = dict(schedule=2, px=4, rows=rows, waves_per_block=waves, flags=flags)
+                say("case tiles ready flags %s window=%d %s" % (rgb.dtype, window, tune))
+                check(run_gpu(gpu, rgb, k=K, window=window, tuning=tune), want)
+    rgb = hi.rectangles_f32(29, 3, 90, 520)
+    want = oracle.harris(rgb, K)
+    src = torch.from_numpy(rgb).cuda()
+    for tdt, fmt in ((torch.float16, "f16"), (torch.bfloat16, "bf16")):
+        out = torch.empty((3, 86, 516), dtype=tdt, device="cuda")
+        gpu.harris_coarsity_typed(src, out, K, tuning=dict(schedule=2, rows=rows, waves_per_block=4, flags=flags))
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy()
+        assert np.all(np.abs(got.astype(np.float64) - _as_f32(oracle.round_to_16bit(want, fmt), fmt)) <= 1e-4 * float(np.abs(want).max()) + 1e-6 + _ulp16(want, fmt))
+    big = hi.white_noise_f32(30, 1, 2200, 1000)                 # thousands of small tiles with flags
+    check(run_gpu(gpu, big, k=K, tuning=dict(schedule=2, rows=rows, waves_per_block=2, flags=flags)), oracle.harris(big, K, nthreads=8))
+
+
 def test_tile_schedule_shapes(gpu, oracle):
     for H, W in SHAPES:
         rgb = hi.white_noise_f32(200 + H + W, 2, H, W)
