@@ -129,7 +129,7 @@ typedef struct harris_tuning {
  */
 int harris_coarsity(const float* rgb, int batch, int H, int W, float k, float* out, void* stream);
 
-/* Same for uint8 images; each value is taken as u/255 (stage a0, then section 4.2). */
+/* Same for uint8 images; each value is taken as u/255 (then section 4.2). */
 int harris_coarsity_u8(const uint8_t* rgb, int batch, int H, int W, float k, float* out, void* stream);
 
 /*

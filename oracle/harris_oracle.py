@@ -107,7 +107,7 @@ def harris(rgb: np.ndarray, k: float = 0.04, sobel_scale: float = 1.0, window: i
 
 
 def gray(rgb: np.ndarray) -> np.ndarray:
-    """Stage a1 on one image [3][H][W] (float32 or float64)."""
+    """Grayscale of one image [3][H][W] (float32 or float64)."""
     a = np.ascontiguousarray(rgb)
     _, H, W = a.shape
     out = np.empty((H, W), dtype=a.dtype)
@@ -126,7 +126,7 @@ def conv3x3(img: np.ndarray, weights: np.ndarray) -> np.ndarray:
 
 
 def sobel(img: np.ndarray, which: str, scale: float = 1.0) -> np.ndarray:
-    """Stage a2: Sx ("x") or Sy ("y") of a 2-D gray image, weights times `scale`."""
+    """Sobel stage: Sx ("x") or Sy ("y") of a 2-D gray image, weights times `scale`."""
     a = np.ascontiguousarray(img)
     H, W = a.shape
     out = np.empty((H - 2, W - 2), dtype=a.dtype)
@@ -135,7 +135,7 @@ def sobel(img: np.ndarray, which: str, scale: float = 1.0) -> np.ndarray:
 
 
 def mul(a: np.ndarray, b: np.ndarray) -> np.ndarray:
-    """Stage a3: pointwise product."""
+    """Products: pointwise product."""
     a = np.ascontiguousarray(a)
     b = np.ascontiguousarray(b, dtype=a.dtype)
     out = np.empty_like(a)
@@ -144,7 +144,7 @@ def mul(a: np.ndarray, b: np.ndarray) -> np.ndarray:
 
 
 def sum3x3(img: np.ndarray) -> np.ndarray:
-    """Stage a4: unweighted 3x3 sums (valid region)."""
+    """Window sums: unweighted 3x3 sums (valid region)."""
     a = np.ascontiguousarray(img)
     H, W = a.shape
     out = np.empty((H - 2, W - 2), dtype=a.dtype)
@@ -153,7 +153,7 @@ def sum3x3(img: np.ndarray) -> np.ndarray:
 
 
 def coarsity(sxx: np.ndarray, sxy: np.ndarray, syy: np.ndarray, k: float) -> np.ndarray:
-    """Stage a5: det - k * trace^2 from the three structure-tensor sums."""
+    """Coarsity: det - k * trace^2 from the three structure-tensor sums."""
     sxx = np.ascontiguousarray(sxx)
     sxy = np.ascontiguousarray(sxy, dtype=sxx.dtype)
     syy = np.ascontiguousarray(syy, dtype=sxx.dtype)

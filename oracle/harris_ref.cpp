@@ -62,7 +62,7 @@ void for_row_bands(int rows, int nthreads, F fn) {
     for (auto& th : pool) th.join();
 }
 
-// Stage a0 (only for 8-bit input): v = u / 255, one correctly rounded division.
+// Conversion (only for 8-bit input): v = u / 255, one correctly rounded division.
 template <typename T>
 void normalise_u8(const uint8_t* u, size_t count, T* v, int nthreads) {
     const int rows = (int)std::min<size_t>(count, 1 << 16);
@@ -72,7 +72,7 @@ void normalise_u8(const uint8_t* u, size_t count, T* v, int nthreads) {
     });
 }
 
-// Stage a1, grayscale: dot product of [0.299 0.587 0.114] with the (R, G, B)
+// Grayscale: dot product of [0.299 0.587 0.114] with the (R, G, B)
 // triple of each pixel, accumulated from 0 in channel order.
 template <typename T>
 void grayscale(const T* rgb, int H, int W, T* gray, int nthreads) {
@@ -91,7 +91,7 @@ void grayscale(const T* rgb, int H, int W, T* gray, int nthreads) {
 // conv3x3 as the Rise listing states it: out[y][x] = sum over i, j of
 // weights[i][j] * in[y+i][x+j], accumulated row-major from 0 (a correlation: the
 // weights are not flipped).  in is H x W, out is (H-2) x (W-2).  Used for the
-// weighted (binomial) window of stage a4, and by the tests to confirm that the
+// weighted (binomial) window of the window-sum stage, and by the tests to confirm that the
 // Sobel pair below equals conv3x3 with the Sx / Sy matrices.
 template <typename T>
 void conv3x3(const T* in, int H, int W, const T weights[3][3], T* out, int nthreads) {
@@ -110,7 +110,7 @@ void conv3x3(const T* in, int H, int W, const T weights[3][3], T* out, int nthre
     });
 }
 
-// Stage a3, pointwise product of two images of the same size.
+// Products: pointwise product of two images of the same size.
 template <typename T>
 void mul2d(const T* a, const T* b, int H, int W, T* out, int nthreads) {
     for_row_bands(H, nthreads, [=](int y0, int y1) {
@@ -118,7 +118,7 @@ void mul2d(const T* a, const T* b, int H, int W, T* out, int nthreads) {
     });
 }
 
-// Stage a4, +3x3: out[y][x] = sum of the nine in[y+i][x+j], accumulated row-major
+// Window sums, +3x3: out[y][x] = sum of the nine in[y+i][x+j], accumulated row-major
 // from 0.  in is H x W, out is (H-2) x (W-2).
 template <typename T>
 void sum3x3(const T* in, int H, int W, T* out, int nthreads) {
@@ -135,7 +135,7 @@ void sum3x3(const T* in, int H, int W, T* out, int nthreads) {
     });
 }
 
-// Stage a5, coarsity: det = sxx*syy - sxy*sxy; trace = sxx + syy;
+// Coarsity: det = sxx*syy - sxy*sxy; trace = sxx + syy;
 // out = det - kappa * trace * trace (evaluated left to right).
 template <typename T>
 void coarsity(const T* sxx, const T* sxy, const T* syy, int H, int W, T kappa, T* out, int nthreads) {
@@ -148,7 +148,7 @@ void coarsity(const T* sxx, const T* sxy, const T* syy, int H, int W, T kappa, T
     });
 }
 
-// Stage a2, the Sobel pair, in the term order of the Halide listing: the six
+// The Sobel pair, in the term order of the Halide listing: the six
 // non-zero taps, each negative tap directly followed by its positive mirror, so
 // that a constant image gives exactly 0.  Weights are scale*{1, 2}; the thesis and
 // its Halide reference use scale = 1/12, the integer matrices are scale = 1.

@@ -206,7 +206,7 @@ __device__ __forceinline__ void store_row_8(const float (&o)[PX], float scale, f
     }
 }
 
-// Stage a0 + a1: element i of plane c as float (8-bit values are converted; their
+// Conversion and grayscale: element i of plane c as float (8-bit values are converted; their
 // 1/255 is folded into the gray weights), then gray = wr*R + wg*G + wb*B.
 template <typename In, int PX>
 __device__ __forceinline__ void gray_row(const RawRow<In, PX>& r, float wr, float wg, float wb, float (&g)[PX]) {
@@ -239,7 +239,7 @@ __device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[
 #pragma unroll
     for (int i = 0; i < PX; ++i) lb.g[GS][i] = gc[i];
     if constexpr (STAGE >= 1) {
-        // Stage a2, separated: down the column from the register ring, then along the row.
+        // Sobel pair, separated: down the column from the register ring, then along the row.
         const float (&ga)[PX] = lb.g[(GS + 1) % 3];   // two rows back
         const float (&gb)[PX] = lb.g[(GS + 2) % 3];   // one row back (the centre row)
         float vs[PX + 2], vd[PX + 2];
@@ -254,14 +254,14 @@ __device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[
         for (int i = 0; i < PX; ++i) {
             float ix = vs[i + 2] - vs[i];                        // [-1 0 1] along the row
             float iy = fmaf(2.0f, vd[i + 1], vd[i] + vd[i + 2]); // [1 2 1] along the row
-            // Stage a3.
+            // Products.
             lb.p[PS][0][i] = ix * ix;
             lb.p[PS][1][i] = ix * iy;
             lb.p[PS][2][i] = iy * iy;
         }
     }
     if constexpr (STAGE >= 2) {
-        // Stage a4, separated: [1 c 1] down the column, then along the row (c = 1 for the
+        // Window sums, separated: [1 c 1] down the column, then along the row (c = 1 for the
         // unweighted sum, 2 for the binomial window).  Along the row neighbouring results
         // share a pair sum, and every value that comes from the lane to the right is an
         // operand of an addition, so that its lane shift rides on that addition.
@@ -293,7 +293,7 @@ __device__ __forceinline__ void row_step(LineBuffers<PX>& lb, const float (&gc)[
                 }
             }
         }
-        // Stage a5.
+        // Coarsity.
 #pragma unroll
         for (int i = 0; i < PX; ++i) {
             float det = fmaf(s[0][i], s[2][i], -(s[1][i] * s[1][i]));

@@ -29,7 +29,7 @@ __device__ __forceinline__ bool pixel(int w, int h, int& x, int& y) {
     return x < w && y < h;
 }
 
-// Stage a0 + a1.  rgb[b][3][H][W] -> gray[b][H][W]; in_scale is 1 (float32) or 1/255 (uint8).
+// Conversion and grayscale.  rgb[b][3][H][W] -> gray[b][H][W]; in_scale is 1 (float32) or 1/255 (uint8).
 template <typename In>
 __global__ void gray_kernel(const In* rgb, float* gray, int H, int W, float in_scale) {
     int x, y;
@@ -48,7 +48,7 @@ __device__ __forceinline__ void sobel_at(const float* in, int w, int y, int x, f
     iy = s * ((r2[0] - r0[0]) + 2.0f * (r2[1] - r0[1]) + (r2[2] - r0[2]));
 }
 
-// Stage a2, one response per launch: which = 0 for Sx, 1 for Sy.  in[b][h+2][w+2] -> out[b][h][w].
+// Sobel stage, one response per launch: which = 0 for Sx, 1 for Sy.  in[b][h+2][w+2] -> out[b][h][w].
 __global__ void sobel_kernel(const float* in, float* out, int h, int w, float s, int which) {
     int x, y;
     if (!pixel(w, h, x, y)) return;
@@ -57,7 +57,7 @@ __global__ void sobel_kernel(const float* in, float* out, int h, int w, float s,
     out[(size_t)blockIdx.z * h * w + (size_t)y * w + x] = which == 0 ? ix : iy;
 }
 
-// Stage a2, both responses.
+// Sobel stage, both responses.
 __global__ void sobel_pair_kernel(const float* in, float* ix_out, float* iy_out, int h, int w, float s) {
     int x, y;
     if (!pixel(w, h, x, y)) return;
@@ -68,7 +68,7 @@ __global__ void sobel_pair_kernel(const float* in, float* ix_out, float* iy_out,
     iy_out[at] = iy;
 }
 
-// Stages a2 + a3.
+// Sobel pair and products.
 __global__ void sobel_products_kernel(const float* in, float* ixx, float* ixy, float* iyy, int h, int w, float s) {
     int x, y;
     if (!pixel(w, h, x, y)) return;
@@ -80,7 +80,7 @@ __global__ void sobel_products_kernel(const float* in, float* ixx, float* ixy, f
     iyy[at] = iy * iy;
 }
 
-// Stage a3, one product per launch.
+// Products, one per launch.
 __global__ void mul_kernel(const float* a, const float* b, float* out, size_t count) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) out[i] = a[i] * b[i];
@@ -91,7 +91,7 @@ __device__ __forceinline__ float window_weight(int i, int j, int binomial) {
     return binomial ? (float)((2 - (i > 1 ? i - 1 : 1 - i)) * (2 - (j > 1 ? j - 1 : 1 - j))) : 1.0f;
 }
 
-// Stage a4, one sum per launch.  in[b][h+2][w+2] -> out[b][h][w].
+// Window sums, one per launch.  in[b][h+2][w+2] -> out[b][h][w].
 __global__ void window_kernel(const float* in, float* out, int h, int w, int binomial) {
     int x, y;
     if (!pixel(w, h, x, y)) return;
@@ -107,13 +107,13 @@ __device__ __forceinline__ float coarsity_of(float sxx, float sxy, float syy, fl
     return det - k * tr * tr;
 }
 
-// Stage a5.
+// Coarsity.
 __global__ void coarsity_kernel(const float* sxx, const float* sxy, const float* syy, float* out, size_t count, float k) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) out[i] = coarsity_of(sxx[i], sxy[i], syy[i], k);
 }
 
-// Stages a4 + a5 from the three product images.
+// Window sums and coarsity from the three product images.
 __global__ void window_coarsity_kernel(const float* ixx, const float* ixy, const float* iyy, float* out, int h, int w, float k, int binomial) {
     int x, y;
     if (!pixel(w, h, x, y)) return;
@@ -130,7 +130,7 @@ __global__ void window_coarsity_kernel(const float* ixx, const float* ixy, const
     out[(size_t)blockIdx.z * h * w + (size_t)y * w + x] = coarsity_of(sxx, sxy, syy, k);
 }
 
-// Stages a3 + a4 + a5 from the two Sobel images.
+// Products, window sums and coarsity from the two Sobel images.
 __global__ void products_window_coarsity_kernel(const float* ix, const float* iy, float* out, int h, int w, float k, int binomial) {
     int x, y;
     if (!pixel(w, h, x, y)) return;
