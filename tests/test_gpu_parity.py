@@ -191,6 +191,29 @@ def test_tile_schedule_ready_flags_instead_of_the_barrier(gpu, oracle, rows):
     check(run_gpu(gpu, big, k=K, tuning=dict(schedule=2, rows=rows, waves_per_block=2, flags=flags)), oracle.harris(big, K, nthreads=8))
 
 
+def test_repeated_launches_give_identical_results(gpu):
+    # The hand-over through LDS (barrier or ready flags) must not depend on timing: 300 launches of
+    # the same image, alternating with launches on other data, bit-identical results.
+    import torch
+    rgb = torch.from_numpy(hi.make("noise_f32_1536x2560")).cuda()
+    other = torch.rand_like(rgb)
+    scratch = torch.empty((1, 1532, 2556), device="cuda")
+    for tune in (None, dict(flags=gpu.HARRIS_TUNE_STREAM_LOADS), dict(schedule=2, rows=4, waves_per_block=4),
+                 dict(schedule=2, rows=5, waves_per_block=16, flags=gpu.HARRIS_TUNE_FLAG_HANDOFF)):
+        say("case repeat 300 launches, tuning %s" % (tune,))
+        first = gpu.harris_coarsity_ex(rgb, K, tuning=tune).clone()
+        out = torch.empty_like(first)
+        for i in range(300):
+            gpu.harris_coarsity_ex(rgb, K, tuning=tune, out=out)
+            if i % 3 == 0:
+                gpu.harris_coarsity_ex(other, K, tuning=tune, out=scratch)
+            if i % 50 == 49:
+                torch.cuda.synchronize()
+                assert torch.equal(out, first)
+        torch.cuda.synchronize()
+        assert torch.equal(out, first)
+
+
 def test_tile_schedule_shapes(gpu, oracle):
     for H, W in SHAPES:
         rgb = hi.white_noise_f32(200 + H + W, 2, H, W)
