@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files without comments, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "32854f2a8e6378f40ca61880795d6a3e32829143287e5dd266b062a3ad73fd6f"
-TRAFFIC_BYTES = {"noise_f32_1536x2560": 65123074, "rects_f32_64x1080x1920": 2195225908,
-                 "blobs_f32_2832x4256": 199621639, "noise_u8_8192x8192": 490165980}
+TRAFFIC_SOURCES_SHA256 = "74863d3f2303b43aea2d13401c036899dd2ceb6f3afbdd558dd1df19bf028ed5"
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 65126858, "rects_f32_64x1080x1920": 2200147392,
+                 "blobs_f32_2832x4256": 200321620, "noise_u8_8192x8192": 489311244}
 
 
 def kernel_sources_sha256():

@@ -85,23 +85,47 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
 
     // Default tile shape.  A problem that one pass over the 256 CUs can hold is fastest as one
     // tile per CU: all CUs then carry the same load and finish together (measured on
-    // 1536x2560: 14.0 us against 14.4 us for small tiles and 14.6 us for the best band shape).
-    // Find the smallest tile of NW wavefronts x RW rows that covers the problem with at most 256
-    // tiles; RW in order of measured preference.  Larger problems take many small tiles of
-    // 4 wavefronts x 4 rows, which keep the memory system busiest (measured on 2832x4256,
-    // 64x1080x1920 and 8192x8192 uint8).
+    // 1536x2560: 12.2 us against 13.5 us for small tiles and 14.6 us for the best band shape).
+    // The tile must cover `need` input rows; it is NW wavefronts x RW rows with the smallest
+    // NW * RW, RW taken from a list in order of measured preference, some with a handicap: short tiles are better off
+    // with few rows per wavefront (a wavefront's RW + 4 row steps are a serial chain, which shows
+    // once the data is there quickly: 768x1024 5.0 us with 5 x 4 against 5.7 us with 10 x 2;
+    // 1024x1024 5.8 us with 6 x 4 against 6.3 us with 8 x 3), tall ones with 8, 6 or 9 (1440x2560 11.8 us
+    // with 8 x 9 against 12.2 us with 10 x 7 and 12.0 us with 5 x 14; but 2160x3840 22.6 us with 10 x 14 against 24.1 us with 9 x 16).  Several images whose tiles would be short are
+    // faster as many small tiles (4 images of 480x640: 5.9 against 6.4 us; 2 of 720x1280: 7.5
+    // against 7.7 us).  Larger problems take many small tiles of 4 wavefronts x 4 rows, which keep
+    // the memory system busiest (measured on 2832x4256, 64x1080x1920 and 8192x8192 uint8).
     int tile_rw = 4, tile_nw = 4;
     if (footprint <= (128LL << 20) && t.px == 4 && batch > 0 && n_strips > 0 && (long long)batch * n_strips <= 256) {
         const long long max_bands = 256 / ((long long)batch * n_strips);
-        const long long need_rows = (n + max_bands - 1) / max_bands + 4;     // input rows per tile
-        static const int kRowsPerWave[] = {8, 9, 10, 6, 5, 4};
+        const long long need = (n + max_bands - 1) / max_bands + 4;         // input rows per tile
+        // {rows per wavefront, rows of handicap}, in order of preference among equals.
+        static const int kShort[][2] = {{5, 0}, {4, 0}, {6, 0}, {0, 0}};
+        static const int kMedium[][2] = {{6, 0}, {5, 0}, {8, 0}, {0, 0}};
+        static const int kTall[][2] = {{8, 0}, {6, 0}, {9, 0}, {10, 3}, {5, 3}, {0, 0}};
+        const int (*list)[2] = need <= 20 ? kShort : need <= 48 ? kMedium : kTall;
         long long best = -1;
-        for (int rw : kRowsPerWave) {
-            long long nw = (need_rows + rw - 1) / rw;
+        for (; (*list)[0] && !(batch > 1 && need <= 48); ++list) {
+            const int rw = (*list)[0];
+            long long nw = (need + rw - 1) / rw;
             if (nw < 2) nw = 2;
             if (nw > 16) continue;
-            if (best < 0 || nw * rw < best) { best = nw * rw; tile_rw = rw; tile_nw = (int)nw; }
+            const long long cost = nw * rw + (*list)[1];
+            if (best < 0 || cost < best) { best = cost; tile_rw = rw; tile_nw = (int)nw; }
         }
+    } else if (can_align && dtype == HARRIS_F32) {
+        // Many tiles of float32 input, measured against 4 x 4 (which stays for 8-bit input, where
+        // every taller tile is slower): one image of 128 to 400 MB, 4 wavefronts x 5 rows
+        // (2832x4256 34.0 against 35.3 us, 4096x4096 46.0 / 48.7, 3000x4000 34.4 / 34.6; several
+        // images of that total size gain nothing); above 400 MB 5 wavefronts x 6 rows up to 1 GB
+        // (4320x7680 97.1 against 105.2 us, 16x1080x1920 98.2 / 102.4, 6x2160x3840 139.7 / 146.0)
+        // and 5 x 8 beyond (32x1080x1920 184.2 / 193.9, 64x1080x1920 374.4 / 380.5, 8192x8192
+        // 182.7 / 181.8, 128x720x1280 334.4 / 332.8), all with the shared rows kept in cache.
+        // (16-bit results beyond 1 GB: 4 x 4, all loads with the default policy; 64x1080x1920 to
+        // binary16 345 us against 349 us with 5 x 6 and 353 us with 5 x 8.)
+        if (footprint > (1LL << 30)) { if (out_dtype == HARRIS_OUT_F32) { tile_rw = 8; tile_nw = 5; } }
+        else if (footprint > (400LL << 20)) { tile_rw = 6; tile_nw = 5; }
+        else if (footprint > (128LL << 20) && batch == 1) { tile_rw = 5; tile_nw = 4; }
     }
 
     long long tile_rows;       // result rows per band or tile
@@ -143,17 +167,16 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     const long long n_tiles = tiles_per_image * batch;
 
     // Load policy, measured.  One tile per CU (at most 256 tiles): everything non-temporal (1536x2560:
-    // 12.2 us against 12.6 us with the shared rows kept).  Many tiles, float32 up to about 400 MB and
-    // 8-bit input: non-temporal except the rows two tiles share, which the default policy keeps in L2
-    // for the second reader (2832x4256: 34.6 us against 37.1 us all-default and 39.7 us
-    // all-non-temporal; 4096x4096: 49.7 / 53.8 / 54.6 us; 32x512x512: 25.7 / 27.0 / 26.8 us; 8192x8192
-    // uint8: 91.1 / 105 / 91.8 us).  Larger float32 problems: everything with the default policy
-    // (64x1080x1920: 379 us against 380 us mixed and 404 us non-temporal; 8192x8192: 181 / 188 / 214 us).
+    // 12.2 us against 12.6 us with the shared rows kept).  Many tiles: non-temporal except the rows
+    // two tiles share, which the default policy keeps in L2 for the second reader (2832x4256: 34.6 us
+    // against 37.1 us all-default and 39.7 us all-non-temporal; 4096x4096: 49.7 / 53.8 / 54.6 us;
+    // 32x512x512: 25.7 / 27.0 / 26.8 us; 8192x8192 uint8: 91.1 / 105 / 91.8 us; 16x1080x1920 with
+    // tiles of 5 x 6: 98.2 / 101.8 us all-default; 64x1080x1920 with 5 x 8: 374.4 / 378.4 us).
     // Bands and lanes narrower than 16 bytes have no mixed policy: default-policy loads from 128 MB on.
     const bool one_tile_per_cu = t.schedule == HARRIS_SCHEDULE_TILES && n_tiles <= 256;
     if (!(t.flags & (HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS))) {
         if (t.flags & HARRIS_TUNE_FLAG_HANDOFF) t.flags |= HARRIS_TUNE_STREAM_LOADS;
-        else if (dtype == HARRIS_F32 && footprint > (400LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
+        else if (dtype == HARRIS_F32 && out_dtype != HARRIS_OUT_F32 && footprint > (1LL << 30)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
         else if (can_align && !one_tile_per_cu) t.flags |= HARRIS_TUNE_STREAM_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS;
         else if (dtype == HARRIS_F32 && footprint > (128LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
         else t.flags |= HARRIS_TUNE_STREAM_LOADS;

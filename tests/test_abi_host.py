@@ -84,14 +84,26 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1080, 1920)[0]["flags"] & pkg.HARRIS_TUNE_FLAG_HANDOFF
     assert not pkg.harris_plan(pkg.HARRIS_U8, 1, 2048, 4096)[0]["flags"] & pkg.HARRIS_TUNE_FLAG_HANDOFF     # 8-bit input keeps the barrier
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=dict(flags=pkg.HARRIS_TUNE_STREAM_LOADS))[0]["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES
-    # beyond one tile per CU: many tiles of 4 wavefronts x 4 rows (12 result rows); cached loads for large float32
+    # short tiles take few rows per wavefront, and several images with short tiles take many small tiles
+    assert [pkg.harris_plan(pkg.HARRIS_F32, 1, 768, 1024)[0][key] for key in ("rows", "waves_per_block")] == [5, 4]
+    assert [pkg.harris_plan(pkg.HARRIS_F32, 1, 1024, 1024)[0][key] for key in ("rows", "waves_per_block")] == [6, 4]
+    assert [pkg.harris_plan(pkg.HARRIS_F32, 1, 2160, 3840)[0][key] for key in ("rows", "waves_per_block")] == [10, 14]
+    several, blocks = pkg.harris_plan(pkg.HARRIS_F32, 4, 480, 640)
+    assert (several["rows"], several["waves_per_block"]) == (4, 4) and blocks == 4 * 3 * 40
+    # beyond one tile per CU: many tiles, non-temporal loads except the rows two tiles share, which stay in L2.
+    # One float32 image of 128 to 400 MB: 4 wavefronts x 5 rows (16 result rows per tile)
     mid, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4256)
-    assert (mid["schedule"], mid["rows"], mid["waves_per_block"]) == (2, 4, 4) and blocks == 18 * 236
-    # between half the last-level cache and about 400 MB: non-temporal loads, but the rows two tiles share stay in L2
+    assert (mid["schedule"], mid["rows"], mid["waves_per_block"]) == (2, 5, 4) and blocks == 18 * 177
     assert mid["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_ALIGNED_STORES
+    assert [pkg.harris_plan(pkg.HARRIS_F32, 2, 2160, 3840)[0][key] for key in ("rows", "waves_per_block")] == [4, 4]
+    # 400 MB to 1 GB: 5 wavefronts x 6 rows; beyond: 5 x 8 (36 result rows per tile)
+    assert [pkg.harris_plan(pkg.HARRIS_F32, 16, 1080, 1920)[0][key] for key in ("rows", "waves_per_block")] == [6, 5]
     big, blocks = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920)
-    assert (big["rows"], big["waves_per_block"]) == (4, 4) and blocks == 64 * 90 * 8
-    assert big["flags"] == pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES
+    assert (big["rows"], big["waves_per_block"]) == (8, 5) and blocks == 64 * 30 * 8
+    assert big["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_ALIGNED_STORES
+    # 16-bit results beyond 1 GB: small tiles, every load with the default policy
+    half, _ = pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_F16, 64, 1080, 1920)
+    assert (half["rows"], half["waves_per_block"]) == (4, 4) and half["flags"] == pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES
     # many tiles below 128 MB as well (32 images of 512x512 cannot be one tile per CU): shared rows kept
     many, blocks = pkg.harris_plan(pkg.HARRIS_F32, 32, 512, 512)
     assert (many["rows"], many["waves_per_block"]) == (4, 4) and blocks > 256
@@ -101,6 +113,7 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     # 8-bit input: non-temporal loads; 35 strips of at most 240 columns cover 8188
     u8, blocks = pkg.harris_plan(pkg.HARRIS_U8, 1, 8192, 8192)
     assert u8["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_ALIGNED_STORES and blocks == 35 * 683
+    assert (u8["rows"], u8["waves_per_block"]) == (4, 4)
     assert pkg.harris_plan(pkg.HARRIS_U8, 1, 64, 98, rgb_align=1)[0]["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES
     # narrower lanes and bands never move strip borders
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 98)[0]["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES
