@@ -73,10 +73,16 @@ typedef enum harris_window {
  *             wavefronts loads a tile of waves_per_block * rows input rows at once and
  *             hands the gray rows that two wavefronts share through LDS.  0 = chosen
  *             from the size.
- *   px        pixels per lane along x: 1, 2, 4 or (BANDS only) 8; must divide W and match
- *             the pointer alignment, else HARRIS_ERR_ARG; 0 = widest of 1, 2, 4 that fits.
+ *   px        pixels per lane along x: 1, 2, 4 or (BANDS only) 8.  A lane's loads and stores
+ *             must be naturally aligned in every row (px divides W, pointers and pitches are
+ *             multiples of the access size), else HARRIS_ERR_ARG; except that TILES with px = 4
+ *             takes any width and any row alignment the element type allows, as long as result
+ *             rows start on 4-byte boundaries and are not 8-bit codes (vector accesses on 4-byte
+ *             boundaries; 8-bit input rows on any byte are loaded as aligned words and
+ *             shifted).  0 = 4 where that holds, else the widest of 2, 1 that fits.
  *   rows      BANDS: result rows per band (>= 1).  TILES: input rows per wavefront: 4 or 8,
- *             and with px = 4 also 5, 6, 9 or 10.  0 = chosen from the size.
+ *             and with px = 4 also 5, 6, 9 or 10 (not for 8-bit input rows off 4-byte
+ *             boundaries).  0 = chosen from the size.
  *   prefetch  BANDS only: input rows kept in flight per wavefront, 2, 3 or 6; 0 = default.
  *   waves_per_block  BANDS: 1, 2 or 4 (2: two bands of a strip that start on shared rows;
  *             4: the same for two adjacent strips).  TILES: 2 to 16.  0 = default.
@@ -106,11 +112,12 @@ typedef struct harris_tuning {
                                         that two vertically adjacent tiles both read (the first and the
                                         last four of a tile) are loaded with the default policy instead,
                                         so that the second reader finds them in L2                   */
-#define HARRIS_TUNE_FLAG_HANDOFF 128u /* TILES with px = 4 and plain non-temporal loads only: a wavefront
+#define HARRIS_TUNE_FLAG_HANDOFF 128u /* TILES with px = 4, plain non-temporal loads and input rows on
+                                        4-byte boundaries only: a wavefront
                                         waits for a ready flag of the wavefront below it instead of
                                         the workgroup's barrier (and a barrier holds the stores back
                                         until the workgroup's loads are in): for few, large tiles     */
-#define HARRIS_TUNE_ALIGNED_STORES 16u /* TILES with px = 4 only: in every result row the border between
+#define HARRIS_TUNE_ALIGNED_STORES 16u /* TILES with px = 4 and naturally aligned lanes only: in every result row the border between
                                         two strips is moved right to the next 64-byte boundary of the
                                         row's address, so that no 64-byte block of the result is
                                         written by two wavefronts; strips are then at most 240

@@ -9,7 +9,7 @@
 
 namespace {
 
-constexpr int kVersion = 300;   // 0.3.0
+constexpr int kVersion = 310;   // 0.3.1
 
 bool power_of_two_aligned(uintptr_t p, unsigned bytes) { return (p & (uintptr_t)(bytes - 1)) == 0; }
 
@@ -17,14 +17,27 @@ int elem_size(int dtype) { return dtype == HARRIS_U8 ? 1 : 4; }
 int out_elem_size(int out_dtype) { return out_dtype == HARRIS_OUT_F32 ? 4 : out_dtype == HARRIS_OUT_U8 ? 1 : 2; }
 bool known_out_dtype(int d) { return d == HARRIS_OUT_F32 || d == HARRIS_OUT_F16 || d == HARRIS_OUT_BF16 || d == HARRIS_OUT_U8; }
 
-// Can every lane load px input elements and store its result columns with single
-// vector accesses?  Loads are px*elem bytes wide up to 16; stores are min(px,4) result elements.
+// Can every lane load px input elements and store its result columns with single, naturally
+// aligned vector accesses?  Loads are px*elem bytes wide up to 16; stores are min(px,4) result elements.
 bool px_fits(int px, int dtype, int out_dtype, int W, int rgb_align, int out_align) {
     if (px < 1 || W % px != 0) return false;
     int load_bytes = px * elem_size(dtype);
     if (load_bytes > 16) load_bytes = 16;
     int store_bytes = (px < 4 ? px : 4) * out_elem_size(out_dtype);
     return rgb_align % load_bytes == 0 && out_align % store_bytes == 0;
+}
+
+// Four pixels per lane without natural alignment (a width that is no multiple of 4, padded
+// rows, an offset view); tile kernel only.  float32 rows start on 4-byte boundaries: buffer
+// accesses of several 32-bit words need only 4-byte alignment, and the hardware checks each
+// word of such an access against the end of the row by itself, so the lane that straddles the
+// end of a row loads zeros beyond it and stores nothing there.  8-bit rows may start on any
+// byte: the kernel loads the aligned words that hold them and shifts.  Results: float32, or
+// 16-bit with rows on 4-byte boundaries (8-bit codes are stored as one word per lane and keep
+// the narrower lanes).
+bool px4_fits_word_aligned(int dtype, int out_dtype, int rgb_align, int out_align) {
+    if (dtype == HARRIS_F32 && rgb_align % 4 != 0) return false;
+    return out_dtype != HARRIS_OUT_U8 && out_align % 4 == 0;
 }
 
 int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int out_align, const harris_tuning* tuning,
@@ -46,11 +59,14 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     if (t.schedule != 0 && t.schedule != HARRIS_SCHEDULE_BANDS && t.schedule != HARRIS_SCHEDULE_TILES) return HARRIS_ERR_ARG;
 
     const int n = H - 4, m = W - 4;
+    const bool tiles_allowed = (t.schedule == 0 || t.schedule == HARRIS_SCHEDULE_TILES) && t.prefetch == 0;
+    const bool word_aligned_px4 = tiles_allowed && px4_fits_word_aligned(dtype, out_dtype, rgb_align, out_align);
     if (t.px == 0) {
         t.px = 1;
-        for (int px = 4; px >= 2; px /= 2)
-            if (px_fits(px, dtype, out_dtype, W, rgb_align, out_align)) { t.px = px; break; }
-    } else if (!((t.px == 1 || t.px == 2 || t.px == 4 || t.px == 8) && px_fits(t.px, dtype, out_dtype, W, rgb_align, out_align))) {
+        if (px_fits(4, dtype, out_dtype, W, rgb_align, out_align) || word_aligned_px4) t.px = 4;
+        else if (px_fits(2, dtype, out_dtype, W, rgb_align, out_align)) t.px = 2;
+    } else if (!((t.px == 1 || t.px == 2 || t.px == 4 || t.px == 8) &&
+                 (px_fits(t.px, dtype, out_dtype, W, rgb_align, out_align) || (t.px == 4 && word_aligned_px4)))) {
         return HARRIS_ERR_ARG;
     }
     if (t.rows < 0 || t.prefetch < 0 || t.waves_per_block < 0) return HARRIS_ERR_ARG;
@@ -58,8 +74,11 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     if (t.schedule == 0) t.schedule = t.px <= 4 && t.prefetch == 0 ? HARRIS_SCHEDULE_TILES : HARRIS_SCHEDULE_BANDS;
     if (out_dtype != HARRIS_OUT_F32 && t.schedule != HARRIS_SCHEDULE_TILES) return HARRIS_ERR_ARG;   // 16- and 8-bit results: tile kernel only
     // Strip borders on 64-byte boundaries of the result rows: the tile kernel with 16-byte lanes.
-    const bool can_align = t.schedule == HARRIS_SCHEDULE_TILES && t.px == 4;
-    if ((t.flags & (HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_KEEP_SHARED_ROWS | HARRIS_TUNE_FLAG_HANDOFF)) && !can_align) return HARRIS_ERR_ARG;
+    // (A lane's stores must then be naturally aligned: borders can only lie between lanes.)
+    const bool tile4 = t.schedule == HARRIS_SCHEDULE_TILES && t.px == 4;
+    const bool can_align = tile4 && px_fits(4, dtype, out_dtype, W, rgb_align, out_align);
+    if ((t.flags & HARRIS_TUNE_ALIGNED_STORES) && !can_align) return HARRIS_ERR_ARG;
+    if ((t.flags & (HARRIS_TUNE_KEEP_SHARED_ROWS | HARRIS_TUNE_FLAG_HANDOFF)) && !tile4) return HARRIS_ERR_ARG;
     // Measured, moved against fixed borders: 378 against 393 us on 64x1080x1920 float32, 12.5
     // against 12.8 us on 1536x2560, 37.0 against 37.3 us on 2832x4256, 89 against 93 us on
     // 8192x8192 uint8.
@@ -75,7 +94,9 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     // to one 64-byte block less a lane (12 float32 or 28 16-bit columns) right of the strip's
     // nominal end, and the wavefront must reach that far.
     const long long border_reach = (t.flags & HARRIS_TUNE_ALIGNED_STORES) ? 64 / out_elem_size(out_dtype) - 4 : 0;
-    const long long max_pitch = (long long)harris_launch::valid_lanes(t.px) * t.px - border_reach;
+    // 8-bit rows loaded as aligned words and shifted: the last lane only supplies bytes to its left neighbour.
+    const bool in_shifted = dtype == HARRIS_U8 && tile4 && !can_align;
+    const long long max_pitch = (long long)harris_launch::valid_lanes(t.px) * t.px - border_reach - (in_shifted ? 4 : 0);
     const long long n_strips = m > 0 ? (m + max_pitch - 1) / max_pitch : 0;
     const long long pitch = n_strips > 0 ? ((m + n_strips - 1) / n_strips + t.px - 1) / t.px * t.px : max_pitch;
 
@@ -103,7 +124,8 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
         static const int kShort[][2] = {{5, 0}, {4, 0}, {6, 0}, {0, 0}};
         static const int kMedium[][2] = {{6, 0}, {5, 0}, {8, 0}, {0, 0}};
         static const int kTall[][2] = {{8, 0}, {6, 0}, {9, 0}, {10, 3}, {5, 3}, {0, 0}};
-        const int (*list)[2] = need <= 20 ? kShort : need <= 48 ? kMedium : kTall;
+        static const int kShifted[][2] = {{4, 0}, {8, 0}, {0, 0}};      // the kernels that exist for shifted 8-bit rows
+        const int (*list)[2] = in_shifted ? kShifted : need <= 20 ? kShort : need <= 48 ? kMedium : kTall;
         long long best = -1;
         for (; (*list)[0] && !(batch > 1 && need <= 48); ++list) {
             const int rw = (*list)[0];
@@ -113,7 +135,7 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
             const long long cost = nw * rw + (*list)[1];
             if (best < 0 || cost < best) { best = cost; tile_rw = rw; tile_nw = (int)nw; }
         }
-    } else if (can_align && dtype == HARRIS_F32) {
+    } else if (tile4 && dtype == HARRIS_F32) {
         // Many tiles of float32 input, measured against 4 x 4 (which stays for 8-bit input, where
         // every taller tile is slower): one image of 128 to 400 MB, 4 wavefronts x 5 rows
         // (2832x4256 34.0 against 35.3 us, 4096x4096 46.0 / 48.7, 3000x4000 34.4 / 34.6; several
@@ -135,6 +157,8 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
         if (t.waves_per_block == 0) t.waves_per_block = 4;
         const bool rows_ok = t.rows == 4 || t.rows == 8 || (t.px == 4 && (t.rows == 5 || t.rows == 6 || t.rows == 9 || t.rows == 10));
         if (!rows_ok || t.waves_per_block < 2 || t.waves_per_block > 16) return HARRIS_ERR_ARG;
+        if (in_shifted && !(t.rows == 4 || t.rows == 8)) return HARRIS_ERR_ARG;
+        if (in_shifted && (t.flags & HARRIS_TUNE_FLAG_HANDOFF)) return HARRIS_ERR_ARG;
         if (t.prefetch != 0) return HARRIS_ERR_ARG;
         if (t.px > 4) return HARRIS_ERR_ARG;                           // 8 rows of 8 pixels per lane do not fit the registers
         tile_rows = (long long)t.rows * t.waves_per_block - 4;
@@ -177,13 +201,13 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     if (!(t.flags & (HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS))) {
         if (t.flags & HARRIS_TUNE_FLAG_HANDOFF) t.flags |= HARRIS_TUNE_STREAM_LOADS;
         else if (dtype == HARRIS_F32 && out_dtype != HARRIS_OUT_F32 && footprint > (1LL << 30)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
-        else if (can_align && !one_tile_per_cu) t.flags |= HARRIS_TUNE_STREAM_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS;
+        else if (tile4 && !one_tile_per_cu) t.flags |= HARRIS_TUNE_STREAM_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS;
         else if (dtype == HARRIS_F32 && footprint > (128LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
         else t.flags |= HARRIS_TUNE_STREAM_LOADS;
         // Ready flags instead of the barrier where tiles are few and tall and the input float32
         // (measured: 1536x2560 12.1 against 12.3 us, 2048x2048 12.7 / 13.2, 2x1536x2560 22.6 / 23.3,
         // 1080x1920 8.4 / 8.4; 720x1280, 3 wavefronts per tile, 6.4 / 6.1; 2048x4096 uint8 18.1 / 15.2).
-        if (one_tile_per_cu && can_align && dtype == HARRIS_F32 && t.waves_per_block >= 5 &&
+        if (one_tile_per_cu && tile4 && dtype == HARRIS_F32 && t.waves_per_block >= 5 &&
             t.flags == (t.flags & ~(HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS)))
             t.flags |= HARRIS_TUNE_FLAG_HANDOFF;
     }
@@ -212,6 +236,7 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
         params->waves_per_block = (unsigned)t.waves_per_block;
         params->flags = t.flags;
         params->out_kind = (unsigned)out_dtype;
+        params->in_shifted = in_shifted ? 1 : 0;
     }
     return HARRIS_OK;
 }

@@ -137,6 +137,34 @@ __device__ __forceinline__ void load_row(RawRow<In, PX>& r, const In* row, size_
     }
 }
 
+// 8-bit rows that start on any byte, four pixels per lane: every lane loads the aligned 32-bit
+// word at its offset from the row's address rounded down to 4 bytes, so no access is
+// misaligned and none leaves the aligned words that hold the row's bytes.  With the row
+// starting `shift` bytes into its first word, a lane's four pixels are the upper bytes of its
+// word and the lower bytes of the word of the lane to its right (realign_row).
+// voff is the lane's first column (a multiple of 4); shift[c] is kept for realign_row.
+template <int AUX>
+__device__ __forceinline__ void load_row_shifted(RawRow<uint8_t, 4>& r, uint32_t (&shift)[3], const uint8_t* row, size_t plane,
+                                                 uint32_t row_bytes, uint32_t voff) {
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+        const uintptr_t a = reinterpret_cast<uintptr_t>(row + c * plane);
+        shift[c] = (uint32_t)a & 3u;
+        const uint32_t bytes = row_bytes ? (row_bytes + shift[c] + 3u) & ~3u : 0u;
+        const __amdgpu_buffer_rsrc_t rs = make_rsrc(reinterpret_cast<const void*>(a & ~(uintptr_t)3), bytes);
+        r.w[c][0] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff, 0, AUX);
+    }
+}
+
+__device__ __forceinline__ void realign_row(RawRow<uint8_t, 4>& r, const uint32_t (&shift)[3]) {
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+        const uint32_t own = r.w[c][0];
+        const uint32_t right = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)own, 0x130, 0xf, 0xf, true);
+        r.w[c][0] = __builtin_amdgcn_alignbyte(right, own, shift[c]);
+    }
+}
+
 // PX results of one lane to a result row described by rs (its size is the row's
 // bytes, or 0 to store nothing); voff is the lane's byte offset in the row.
 template <int PX>
@@ -437,8 +465,12 @@ __device__ __forceinline__ void pin_values(float (&v)[PX]) {
 // arrives long after the first's, and without the flags every wavefront's last four rows would
 // wait for it and then be computed by all at once (1536x2560: 12.2 against 12.4 us); with many
 // small tiles the barrier is faster (720x1280: 6.1 against 6.4 us).
-template <typename In, int PX, int RW, int LAUX, bool BINOM, bool HANDOFF>
+//
+// SHIFTED (8-bit input, four pixels per lane): rows start on any byte and are loaded as the
+// aligned 32-bit words that hold them (load_row_shifted, realign_row).
+template <typename In, int PX, int RW, int LAUX, bool BINOM, bool HANDOFF, bool SHIFTED = false>
 __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::Params p) {
+    static_assert(!SHIFTED || (std::is_same<In, uint8_t>::value && PX == 4), "shifted rows: 8-bit input, four pixels per lane");
     extern __shared__ __align__(16) float halo_lds[];           // [NW][4][64][PX]
     __shared__ unsigned ready[16];                              // HANDOFF: wavefront w has published its four rows
 
@@ -471,7 +503,11 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
     const int out_rows = max(0, min(RW, y_end - y_wave));       // result rows this wavefront stores
 
     const unsigned col = (unsigned)strip * p.strip_pitch + lane * PX;
-    const unsigned lcol = min(col, (unsigned)(p.W - PX));
+    // Lanes right of the row load what the last lane with a column of the row loads (nobody
+    // uses what they compute).  That lane may straddle the end of the row (a width that is no
+    // multiple of PX): it gets zeros for the words beyond the end, since each 32-bit word of a
+    // load is checked against the descriptor's size by itself.
+    const unsigned lcol = min(col, ((unsigned)p.W - 1u) & ~(unsigned)(PX - 1));
     // Results are float32, 16-bit or 8-bit: esh is log2 of a result element's bytes.
     const unsigned esh = p.out_kind == HARRIS_OUT_F32 ? 2u : p.out_kind == HARRIS_OUT_U8 ? 0u : 1u;
     // With aligned stores the border between this strip and the next lies, in each result row,
@@ -491,12 +527,25 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 
     // All RW rows of this wavefront at once; rows below the image get an empty descriptor.
     RawRow<In, PX> raw[RW];
+    [[maybe_unused]] uint32_t shift[RW][3];                     // SHIFTED: byte offset of each row in its first word
+    // Shifted rows: every lane within reach loads the word at its own column (one lane further
+    // right than otherwise, which supplies the last lane's missing bytes); the descriptor's
+    // size stops the lanes right of the row.
+    [[maybe_unused]] const uint32_t shifted_voff = lane * PX < p.strip_pitch + 8 ? col : 0x80000000u;
     static_for<0, RW>([&](auto tt) {
         constexpr int t = decltype(tt)::value;
         const int r = y_wave + t;
         const In* row_in = img_in + (size_t)min(r, p.H - 1) * (size_t)p.in_row_pitch;
         const uint32_t row_bytes = r < p.H ? in_row_bytes : 0u;
-        if constexpr (LAUX == kAuxKeepShared) {
+        if constexpr (SHIFTED) {
+            if constexpr (LAUX == kAuxKeepShared) {
+                const bool shared = (t < 4 && wave == 0) || (t >= RW - 4 && wave + 1 == n_waves);
+                if (shared) load_row_shifted<kAuxDefault>(raw[t], shift[t], row_in, plane, row_bytes, shifted_voff);
+                else load_row_shifted<kAuxNonTemporal>(raw[t], shift[t], row_in, plane, row_bytes, shifted_voff);
+            } else {
+                load_row_shifted<LAUX>(raw[t], shift[t], row_in, plane, row_bytes, shifted_voff);
+            }
+        } else if constexpr (LAUX == kAuxKeepShared) {
             const bool shared = (t < 4 && wave == 0) || (t >= RW - 4 && wave + 1 == n_waves);
             if (shared) load_row<In, PX, kAuxDefault>(raw[t], row_in, plane, row_bytes, load_voff);
             else load_row<In, PX, kAuxNonTemporal>(raw[t], row_in, plane, row_bytes, load_voff);
@@ -546,6 +595,7 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 
     static_for<0, RW>([&](auto tt) {
         constexpr int t = decltype(tt)::value;
+        if constexpr (SHIFTED) realign_row(raw[t], shift[t]);
         gray_row<In, PX>(raw[t], p.wr, p.wg, p.wb, gc);
         if constexpr (t < 4) {
 #pragma unroll
@@ -631,6 +681,25 @@ template <typename In, int PX, int RW>
 hipError_t launch_tiles(const harris_launch::Params& p, dim3 grid, dim3 block, hipStream_t stream) {
     const size_t lds = (size_t)(block.x / kWave) * 4 * kWave * PX * sizeof(float);
     const bool cached = p.flags & HARRIS_TUNE_CACHED_LOADS;
+    if (p.in_shifted) {
+        // 8-bit rows on any byte: kernels for 4 and 8 rows per wavefront, barrier hand-over.
+        if constexpr (std::is_same<In, uint8_t>::value && PX == 4 && (RW == 4 || RW == 8)) {
+            if (p.flags & HARRIS_TUNE_FLAG_HANDOFF) return hipErrorInvalidValue;
+            const bool keep = p.flags & HARRIS_TUNE_KEEP_SHARED_ROWS;
+            if (p.binomial) {
+                if (keep) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxKeepShared, true, false, true>), grid, block, lds, stream, p);
+                else if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, true, false, true>), grid, block, lds, stream, p);
+                else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, true, false, true>), grid, block, lds, stream, p);
+            } else {
+                if (keep) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxKeepShared, false, false, true>), grid, block, lds, stream, p);
+                else if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, false, false, true>), grid, block, lds, stream, p);
+                else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, false, false, true>), grid, block, lds, stream, p);
+            }
+            return hipGetLastError();
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     if constexpr (PX == 4) {
         // Kernels that exist for 16-byte lanes only (the planner asks for them nowhere else).
         if (p.flags & HARRIS_TUNE_FLAG_HANDOFF) {

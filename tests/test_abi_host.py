@@ -41,11 +41,31 @@ def test_version_and_strerror(pkg):
 def test_plan_picks_widest_vector_path(pkg):
     shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
     assert shape["px"] == 4 and blocks > 128 and shape["rows"] >= 4
-    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 98)[0]["px"] == 2          # W even, not a multiple of 4
-    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 97)[0]["px"] == 1          # odd W
-    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 96, rgb_align=4)[0]["px"] == 1   # misaligned input
-    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 96, out_align=8)[0]["px"] == 2   # misaligned result
-    assert pkg.harris_plan(pkg.HARRIS_U8, 1, 64, 96, rgb_align=1)[0]["px"] == 1
+    # The tile kernel keeps four pixels per lane for any width and any row alignment the element
+    # type allows (word-aligned vector accesses; 8-bit rows loaded as aligned words and shifted);
+    # strip borders then stay where they are.
+    for args, kw in (((pkg.HARRIS_F32, 1, 64, 98), {}), ((pkg.HARRIS_F32, 1, 64, 97), {}),
+                     ((pkg.HARRIS_F32, 1, 64, 96), dict(rgb_align=4)), ((pkg.HARRIS_F32, 1, 64, 96), dict(out_align=8)),
+                     ((pkg.HARRIS_U8, 1, 64, 96), dict(rgb_align=1)), ((pkg.HARRIS_U8, 1, 64, 99), dict(rgb_align=1, out_align=4))):
+        shape = pkg.harris_plan(*args, **kw)[0]
+        assert shape["px"] == 4 and shape["schedule"] == pkg.HARRIS_SCHEDULE_TILES and shape["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES, (args, kw)
+        with pytest.raises(pkg.HarrisError) as e:           # moved borders need naturally aligned lanes
+            pkg.harris_plan(*args, tuning=dict(flags=pkg.HARRIS_TUNE_ALIGNED_STORES), **kw)
+        assert e.value.status == -3
+    # shifted 8-bit rows: strips of at most 248 columns (the last lane only supplies bytes): 500 columns take 3, not 2
+    plain = dict(rows=4, waves_per_block=4, flags=pkg.HARRIS_TUNE_PLAIN_STORES)
+    assert pkg.harris_plan(pkg.HARRIS_U8, 1, 64, 504, tuning=plain)[1] == 2 * 5
+    assert pkg.harris_plan(pkg.HARRIS_U8, 1, 64, 504, rgb_align=1, tuning=plain)[1] == 3 * 5
+    # the band schedule keeps naturally aligned lanes: narrower ones for such rows
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 98, tuning=dict(schedule=1))[0]["px"] == 2
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 97, tuning=dict(schedule=1))[0]["px"] == 1
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 96, rgb_align=4, tuning=dict(schedule=1))[0]["px"] == 1
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 64, 96, out_align=8, tuning=dict(schedule=1))[0]["px"] == 2
+    assert pkg.harris_plan(pkg.HARRIS_U8, 1, 64, 96, rgb_align=1, tuning=dict(schedule=1))[0]["px"] == 1
+    # 8-bit codes are one word per lane: rows of codes off 4-byte boundaries take narrower lanes
+    assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_U8, 1, 64, 98, out_align=1)[0]["px"] == 1
+    assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_F16, 1, 64, 98, out_align=4)[0]["px"] == 4
+    assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_F16, 1, 64, 97, out_align=2)[0]["px"] == 1
     assert pkg.harris_plan(pkg.HARRIS_U8, 1, 8192, 8192)[0]["px"] == 4
 
 
@@ -109,7 +129,9 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     assert (many["rows"], many["waves_per_block"]) == (4, 4) and blocks > 256
     assert many["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_ALIGNED_STORES
     # lanes narrower than 16 bytes have no mixed policy: default-policy loads from 128 MB on
-    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4258)[0]["flags"] == pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4258, tuning=dict(px=2))[0]["flags"] == pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES
+    # a width that is no multiple of 4 keeps the 16-byte lanes and their policy, with fixed strip borders
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4258)[0]["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_PLAIN_STORES
     # 8-bit input: non-temporal loads; 35 strips of at most 240 columns cover 8188
     u8, blocks = pkg.harris_plan(pkg.HARRIS_U8, 1, 8192, 8192)
     assert u8["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_ALIGNED_STORES and blocks == 35 * 683
@@ -147,8 +169,8 @@ def test_plan_rejects_bad_arguments(pkg):
         with pytest.raises(E) as e:
             pkg.harris_plan(0, 1, 64, 64, tuning=bad)
         assert e.value.status == -3
-    with pytest.raises(E):                          # px = 4 needs W % 4 == 0
-        pkg.harris_plan(0, 1, 64, 98, tuning=dict(px=4))
+    with pytest.raises(E):                          # px = 4 in the band schedule needs W % 4 == 0
+        pkg.harris_plan(0, 1, 64, 98, tuning=dict(schedule=1, px=4))
 
 
 def test_plan_for_16_bit_results(pkg):
@@ -163,7 +185,7 @@ def test_plan_for_16_bit_results(pkg):
     assert small["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES and (small["rows"], small["waves_per_block"]) == (8, 9) and blocks == 253
     assert pkg.harris_plan_typed(pkg.HARRIS_U8, BF16, 1, 8192, 8192)[0]["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, F16, 1, 1536, 2560, tuning=dict(flags=pkg.HARRIS_TUNE_ALIGNED_STORES))[1] % 12 == 0
-    assert pkg.harris_plan_typed(pkg.HARRIS_F32, BF16, 1, 64, 96, out_align=4)[0]["px"] == 2
+    assert pkg.harris_plan_typed(pkg.HARRIS_F32, BF16, 1, 64, 96, out_align=4)[0]["px"] == 4      # word-aligned 8-byte stores
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, BF16, 1, 64, 96, out_align=2)[0]["px"] == 1
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_F32, 1, 1536, 2560) == pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
     for bad in (dict(out_dtype=4), dict(out_dtype=F16, tuning=dict(schedule=1)), dict(out_dtype=F16, tuning=dict(prefetch=3)),

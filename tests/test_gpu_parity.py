@@ -242,7 +242,7 @@ def test_extreme_aspect_ratios_and_many_small_images(gpu, oracle, batch, H, W):
         check(run_gpu(gpu, rgb, k=K, tuning=tune), want)
 
 
-def test_misaligned_base_pointers_take_the_narrow_paths(gpu, oracle):
+def test_misaligned_base_pointers(gpu, oracle):
     import torch
     H, W = 21, 300
     rgb = hi.white_noise_f32(9, 1, H, W)
@@ -271,6 +271,121 @@ def test_misaligned_base_pointers_take_the_narrow_paths(gpu, oracle):
         out = gpu.harris_coarsity_u8(uflat[off:off + u8.size].view(1, 3, H, W), K)
         torch.cuda.synchronize()
         check(out.cpu().numpy(), oracle.harris(u8, K))
+
+
+def test_misaligned_base_pointers_on_the_narrow_paths(gpu, oracle):
+    # The kernels with 1 and 2 pixels per lane, asked for explicitly, in both schedules.
+    import torch
+    H, W = 21, 300
+    rgb = hi.white_noise_f32(11, 1, H, W)
+    want = oracle.harris(rgb, K)
+    flat = torch.zeros(rgb.size + 8, device="cuda")
+    for off, px in ((1, 1), (2, 2), (2, 1), (3, 1)):
+        flat[off:off + rgb.size] = torch.from_numpy(rgb.reshape(-1)).cuda()
+        t = flat[off:off + rgb.size].view(1, 3, H, W)
+        for schedule in (1, 2):
+            say("case f32 input offset by %d floats, px %d, schedule %d" % (off, px, schedule))
+            out = gpu.harris_coarsity_ex(t, K, tuning=dict(schedule=schedule, px=px))
+            torch.cuda.synchronize()
+            check(out.cpu().numpy(), want)
+    u8 = hi.white_noise_u8(12, 1, H, W)
+    want8 = oracle.harris(u8, K)
+    uflat = torch.zeros(u8.size + 8, dtype=torch.uint8, device="cuda")
+    for off, px in ((1, 1), (2, 2), (3, 1)):
+        uflat[off:off + u8.size] = torch.from_numpy(u8.reshape(-1)).cuda()
+        for schedule in (1, 2):
+            say("case u8 input offset by %d bytes, px %d, schedule %d" % (off, px, schedule))
+            out = gpu.harris_coarsity_ex(uflat[off:off + u8.size].view(1, 3, H, W), K, tuning=dict(schedule=schedule, px=px))
+            torch.cuda.synchronize()
+            check(out.cpu().numpy(), want8)
+
+
+@pytest.mark.parametrize("W", [97, 98, 99, 261, 515, 1026])
+def test_any_width_and_row_alignment_with_16_byte_lanes(gpu, oracle, W):
+    # The tile kernel keeps four pixels per lane when rows are not naturally aligned: float32
+    # rows on any 4-byte boundary (vector accesses need no more; the lane that straddles the
+    # end of a row loads zeros beyond it and stores nothing there), 8-bit rows on any byte
+    # (loaded as the aligned words that hold them, then shifted).  Input and result are views
+    # inside larger buffers: guard bands show that nothing else is written, and whatever a
+    # straddling access did would stay inside an allocation.
+    import torch
+    B, H = 2, 37
+    n, m = H - 4, W - 4
+    G = 1024
+    rgb = hi.white_noise_f32(90 + W, B, H, W)
+    want = oracle.harris(rgb, K)
+    wantb = oracle.harris(rgb, K, window=1)
+    u8 = hi.white_noise_u8(91 + W, B, H, W)
+    want8 = oracle.harris(u8, K)
+    obuf = torch.empty(G + B * n * m + 3 + G, device="cuda")
+
+    def run(src, off_out, expect, **kw):
+        obuf.fill_(float("nan"))
+        out = obuf[G + off_out:G + off_out + B * n * m].view(B, n, m)
+        gpu.harris_coarsity_ex(src, K, out=out, **kw)
+        torch.cuda.synchronize()
+        check(out.cpu().numpy(), expect)
+        rest = obuf.clone()
+        rest[G + off_out:G + off_out + B * n * m] = float("nan")
+        assert bool(torch.isnan(rest).all())                     # guard bands untouched
+
+    ibuf = torch.full((G + rgb.size + 3 + G,), 0.5, device="cuda")
+    for off_in, off_out in ((0, 0), (1, 3), (2, 1), (3, 2)):
+        src = ibuf[G + off_in:G + off_in + rgb.size].view(B, 3, H, W)
+        src.copy_(torch.from_numpy(rgb))
+        shape, _ = gpu.harris_plan(gpu.HARRIS_F32, B, H, W, rgb_align=4, out_align=4)
+        assert shape["px"] == 4 and shape["schedule"] == gpu.HARRIS_SCHEDULE_TILES
+        say("case f32 W=%d input offset %d result offset %d floats, default plan" % (W, off_in, off_out))
+        run(src, off_out, want)
+        if off_in != 1:
+            continue
+        for rows, waves, flags in ((4, 4, 0), (5, 2, gpu.HARRIS_TUNE_STREAM_LOADS | gpu.HARRIS_TUNE_KEEP_SHARED_ROWS), (6, 3, gpu.HARRIS_TUNE_CACHED_LOADS),
+                                   (8, 2, gpu.HARRIS_TUNE_FLAG_HANDOFF), (9, 2, 0), (10, 2, gpu.HARRIS_TUNE_FLAG_HANDOFF)):
+            say("case f32 W=%d tile %dx%d flags %d" % (W, waves, rows, flags))
+            run(src, off_out, want, tuning=dict(schedule=2, px=4, rows=rows, waves_per_block=waves, flags=flags))
+        say("case f32 W=%d binomial window" % W)
+        run(src, off_out, wantb, window=1)
+        with pytest.raises(gpu.HarrisError):                     # moved strip borders need naturally aligned lanes
+            gpu.harris_coarsity_ex(src, K, tuning=dict(flags=gpu.HARRIS_TUNE_ALIGNED_STORES))
+        with pytest.raises(gpu.HarrisError):                     # and so does the band schedule with px = 4
+            gpu.harris_coarsity_ex(src, K, tuning=dict(schedule=1, px=4))
+
+    ubuf = torch.full((G + u8.size + 3 + G,), 200, dtype=torch.uint8, device="cuda")
+    for off_in in (0, 1, 2, 3):
+        src = ubuf[G + off_in:G + off_in + u8.size].view(B, 3, H, W)
+        src.copy_(torch.from_numpy(u8))
+        say("case u8 W=%d input offset %d bytes, default plan" % (W, off_in))
+        run(src, off_in, want8)
+        for rows, waves, flags in ((4, 3, gpu.HARRIS_TUNE_STREAM_LOADS | gpu.HARRIS_TUNE_KEEP_SHARED_ROWS), (8, 2, gpu.HARRIS_TUNE_CACHED_LOADS), (8, 3, gpu.HARRIS_TUNE_STREAM_LOADS)):
+            say("case u8 W=%d input offset %d tile %dx%d flags %d" % (W, off_in, waves, rows, flags))
+            run(src, off_in, want8, tuning=dict(schedule=2, px=4, rows=rows, waves_per_block=waves, flags=flags))
+    src = ubuf[G + 1:G + 1 + u8.size].view(B, 3, H, W)
+    src.copy_(torch.from_numpy(u8))
+    say("case u8 W=%d binomial window" % W)
+    run(src, 0, oracle.harris(u8, K, window=1), window=1)
+    for bad in (dict(schedule=2, px=4, rows=5), dict(schedule=2, px=4, rows=8, flags=gpu.HARRIS_TUNE_FLAG_HANDOFF)):
+        with pytest.raises(gpu.HarrisError):                     # shifted rows: kernels for 4 and 8 rows, barrier only
+            gpu.harris_coarsity_ex(src, K, tuning=bad)
+    # 16-bit results on 4-byte boundaries keep the wide lanes too (8-byte stores)
+    if W % 2 == 0:
+        f32src = ibuf[G + 1:G + 1 + rgb.size].view(B, 3, H, W)
+        f32src.copy_(torch.from_numpy(rgb))
+        hbuf = torch.full((G + B * n * m + 2 + G,), float("nan"), dtype=torch.float16, device="cuda")
+        for off_out in (0, 2):
+            say("case f16 result W=%d offset %d" % (W, off_out))
+            hbuf.fill_(float("nan"))
+            out16 = hbuf[G + off_out:G + off_out + B * n * m].view(B, n, m)
+            assert gpu.harris_plan_typed(gpu.HARRIS_F32, gpu.HARRIS_OUT_F16, B, H, W, rgb_align=4, out_align=4)[0]["px"] == 4
+            gpu.harris_coarsity_typed(f32src, out16, K)
+            out32 = torch.empty((B, n, m), device="cuda")
+            gpu.harris_coarsity_typed(f32src, out32, K)
+            torch.cuda.synchronize()
+            bits = out16.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+            check(out32.cpu().numpy(), want)
+            assert np.array_equal(bits, oracle.round_to_16bit(out32.cpu().numpy(), "f16"))
+            rest = hbuf.clone()
+            rest[G + off_out:G + off_out + B * n * m] = float("nan")
+            assert bool(torch.isnan(rest).all())
 
 
 @pytest.mark.parametrize("W", [744, 1000, 488])
