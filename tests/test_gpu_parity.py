@@ -753,6 +753,53 @@ def test_runs_on_a_side_stream(gpu, oracle):
     check(out.cpu().numpy(), oracle.harris(rgb, K))
 
 
+def test_captured_in_a_graph_and_replayed(gpu, oracle):
+    # The library allocates nothing and never synchronises, so its launches can be captured.
+    # A graph of three launches (barrier hand-over, ready flags, 8-bit input through the shifted
+    # loads) is replayed several times with fresh inputs and eager work in between; every
+    # replay is checked against the oracle and against the eager launch, bit for bit.
+    import torch
+    H, W = 150, 1000
+    a = torch.empty((1, 3, H, W), device="cuda")
+    b = torch.empty((1, 3, H, W - 1), dtype=torch.uint8, device="cuda")
+    out_a = torch.empty((1, H - 4, W - 4), device="cuda")
+    out_f = torch.empty((1, H - 4, W - 4), device="cuda")
+    out_b = torch.empty((1, H - 4, W - 5), device="cuda")
+    flags_tuning = dict(schedule=2, px=4, rows=8, waves_per_block=5, flags=gpu.HARRIS_TUNE_FLAG_HANDOFF)
+    a.copy_(torch.from_numpy(hi.white_noise_f32(400, 1, H, W)))
+    b.copy_(torch.from_numpy(hi.white_noise_u8(401, 1, H, W - 1)))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                # one eager pass on the capture stream first
+        gpu.harris_coarsity_ex(a, K, out=out_a)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        gpu.harris_coarsity_ex(a, K, out=out_a)
+        gpu.harris_coarsity_ex(a, K, out=out_f, tuning=flags_tuning)
+        gpu.harris_coarsity_ex(b, K, out=out_b)
+    for replay in range(4):
+        say("case graph replay %d" % replay)
+        rgb = hi.white_noise_f32(410 + replay, 1, H, W)
+        u8 = hi.white_noise_u8(420 + replay, 1, H, W - 1)
+        a.copy_(torch.from_numpy(rgb))
+        b.copy_(torch.from_numpy(u8))
+        for o in (out_a, out_f, out_b):
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got_a, got_f, got_b = out_a.cpu().numpy(), out_f.cpu().numpy(), out_b.cpu().numpy()
+        check(got_a, oracle.harris(rgb, K))
+        check(got_f, oracle.harris(rgb, K))
+        check(got_b, oracle.harris(u8, K))
+        eager_a = gpu.harris_coarsity_ex(a, K)                   # eager work between the replays
+        eager_f = gpu.harris_coarsity_ex(a, K, tuning=flags_tuning)
+        eager_b = gpu.harris_coarsity_ex(b, K)
+        torch.cuda.synchronize()
+        assert np.array_equal(got_a, eager_a.cpu().numpy()) and np.array_equal(got_f, eager_f.cpu().numpy()) and np.array_equal(got_b, eager_b.cpu().numpy())
+
+
 # ---------------------------------------------------------------- full sizes, in the launch shape the benchmark times
 
 @pytest.mark.parametrize("name", ["noise_f32_1536x2560", "blobs_f32_2832x4256", "noise_u8_8192x8192"])
