@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files without comments, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "38174d9347ab2d8edeb24def8b9559b60c32af22b8d9ff4b36ac4ebda70a944c"
-TRAFFIC_BYTES = {"noise_f32_1536x2560": 65140107, "rects_f32_64x1080x1920": 2200072470,
-                 "blobs_f32_2832x4256": 200185694, "noise_u8_8192x8192": 489780090}
+TRAFFIC_SOURCES_SHA256 = "ff8563d2b3769a39808ce88ea4c29eff1ba4367459f5169b4df473f2d3326452"
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 65140289, "rects_f32_64x1080x1920": 2199898589,
+                 "blobs_f32_2832x4256": 200194169, "noise_u8_8192x8192": 489677536}
 
 
 def kernel_sources_sha256():

@@ -108,14 +108,14 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     // tile per CU: all CUs then carry the same load and finish together (measured on
     // 1536x2560: 12.2 us against 13.5 us for small tiles and 14.6 us for the best band shape).
     // The tile must cover `need` input rows; it is NW wavefronts x RW rows with the smallest
-    // NW * RW, RW taken from a list in order of measured preference, some with a handicap: short tiles are better off
-    // with few rows per wavefront (a wavefront's RW + 4 row steps are a serial chain, which shows
-    // once the data is there quickly: 768x1024 5.0 us with 5 x 4 against 5.7 us with 10 x 2;
-    // 1024x1024 5.8 us with 6 x 4 against 6.3 us with 8 x 3), tall ones with 8, 6 or 9 (1440x2560 11.8 us
-    // with 8 x 9 against 12.2 us with 10 x 7 and 12.0 us with 5 x 14; but 2160x3840 22.6 us with 10 x 14 against 24.1 us with 9 x 16).  Several images whose tiles would be short are
-    // faster as many small tiles (4 images of 480x640: 5.9 against 6.4 us; 2 of 720x1280: 7.5
-    // against 7.7 us).  Larger problems take many small tiles of 4 wavefronts x 4 rows, which keep
-    // the memory system busiest (measured on 2832x4256, 64x1080x1920 and 8192x8192 uint8).
+    // NW * RW, RW taken from a list in order of measured preference, some with a handicap.
+    // Short tiles are better off with few rows per wavefront (a wavefront's RW + 4 row steps are
+    // a serial chain, which shows once the data is there quickly: 768x1024 5.0 us with 5 x 4
+    // against 5.7 us with 10 x 2; 1024x1024 5.8 us with 6 x 4 against 6.3 us with 8 x 3), tall
+    // ones with 8, 6 or 9 (1440x2560 11.8 us with 8 x 9 against 12.2 us with 10 x 7 and 12.0 us
+    // with 5 x 14; but 2160x3840 22.6 us with 10 x 14 against 24.1 us with 9 x 16).
+    // Larger problems take many small tiles, which keep the memory system busiest (measured
+    // on 2832x4256, 64x1080x1920 and 8192x8192 uint8).
     int tile_rw = 4, tile_nw = 4;
     if (footprint <= (128LL << 20) && t.px == 4 && batch > 0 && n_strips > 0 && (long long)batch * n_strips <= 256) {
         const long long max_bands = 256 / ((long long)batch * n_strips);
@@ -124,10 +124,18 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
         static const int kShort[][2] = {{5, 0}, {4, 0}, {6, 0}, {0, 0}};
         static const int kMedium[][2] = {{6, 0}, {5, 0}, {8, 0}, {0, 0}};
         static const int kTall[][2] = {{8, 0}, {6, 0}, {9, 0}, {10, 3}, {5, 3}, {0, 0}};
+        // 8-bit input has more arithmetic per byte and does better with fewer rows per wavefront
+        // (1536x2560: 7.8 us with 12 x 6 against 8.8 us with 9 x 8; 2160x3840: 13.2 us with 16 x 9
+        // against 14.1 us with 14 x 10).
+        static const int kTall8[][2] = {{6, 0}, {5, 3}, {8, 2}, {9, 2}, {10, 6}, {0, 0}};
         static const int kShifted[][2] = {{4, 0}, {8, 0}, {0, 0}};      // the kernels that exist for shifted 8-bit rows
-        const int (*list)[2] = in_shifted ? kShifted : need <= 20 ? kShort : need <= 48 ? kMedium : kTall;
+        const int (*list)[2] = in_shifted ? kShifted : need <= 20 ? kShort : need <= 48 ? kMedium : dtype == HARRIS_U8 ? kTall8 : kTall;
+        // Tiles of 26 to 32 rows (40 for 8-bit input), and several images with tiles of up to
+        // 48 rows, are faster as many small tiles (960x1280: 6.2 against 6.7 us, 8-bit 5.1 / 5.6;
+        // 1080x1920 8-bit: 5.5 / 5.9, but float32 8.4 / 8.2).
+        const bool small_tiles = (batch > 1 && need <= 48) || (need >= 26 && need <= (dtype == HARRIS_U8 ? 40 : 32));
         long long best = -1;
-        for (; (*list)[0] && !(batch > 1 && need <= 48); ++list) {
+        for (; (*list)[0] && !small_tiles; ++list) {
             const int rw = (*list)[0];
             long long nw = (need + rw - 1) / rw;
             if (nw < 2) nw = 2;

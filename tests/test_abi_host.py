@@ -108,6 +108,12 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     assert [pkg.harris_plan(pkg.HARRIS_F32, 1, 768, 1024)[0][key] for key in ("rows", "waves_per_block")] == [5, 4]
     assert [pkg.harris_plan(pkg.HARRIS_F32, 1, 1024, 1024)[0][key] for key in ("rows", "waves_per_block")] == [6, 4]
     assert [pkg.harris_plan(pkg.HARRIS_F32, 1, 2160, 3840)[0][key] for key in ("rows", "waves_per_block")] == [10, 14]
+    # 8-bit input: fewer rows per wavefront for tall tiles
+    assert [pkg.harris_plan(pkg.HARRIS_U8, 1, 1536, 2560)[0][key] for key in ("rows", "waves_per_block")] == [6, 12]
+    assert [pkg.harris_plan(pkg.HARRIS_U8, 1, 2160, 3840)[0][key] for key in ("rows", "waves_per_block")] == [9, 16]
+    # tiles of 26 to 32 rows (40 for 8-bit input) give way to many small tiles
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 960, 1280)[1] == 6 * 80 and pkg.harris_plan(pkg.HARRIS_F32, 1, 1080, 1920)[1] <= 256
+    assert pkg.harris_plan(pkg.HARRIS_U8, 1, 1080, 1920)[1] == 8 * 90
     several, blocks = pkg.harris_plan(pkg.HARRIS_F32, 4, 480, 640)
     assert (several["rows"], several["waves_per_block"]) == (4, 4) and blocks == 4 * 3 * 40
     # beyond one tile per CU: many tiles, non-temporal loads except the rows two tiles share, which stay in L2.
