@@ -184,16 +184,21 @@ __device__ __forceinline__ void store_row(const float (&o)[PX], __amdgpu_buffer_
 }
 
 // float32 -> bit pattern of the nearest binary16 / bfloat16 value (ties to even, overflow to
-// infinity).  binary16 by the hardware conversion (round-to-nearest-even is the mode HIP
-// kernels run in); bfloat16 by adding half of the dropped part's range, plus the lowest kept
-// bit so that ties go to even, and truncating; NaN stays NaN.
+// infinity, NaN stays NaN), by the hardware conversions: round-to-nearest-even is the mode
+// HIP kernels run in, and gfx950 converts two float32 values to a bfloat16 pair in one
+// instruction.
 __device__ __forceinline__ uint32_t to_f16_bits(float x) {
     return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)x);
 }
 __device__ __forceinline__ uint32_t to_bf16_bits(float x) {
-    const uint32_t u = __float_as_uint(x);
-    const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-    return (u & 0x7fffffffu) > 0x7f800000u ? ((u >> 16) | 0x40u) : rounded;
+    return (uint32_t)__builtin_bit_cast(unsigned short, (__bf16)x);
+}
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// lo in bits 0..15, hi in bits 16..31
+__device__ __forceinline__ uint32_t to_bf16_pair(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // PX results of one lane as 16-bit values (BF: bfloat16, else binary16); voff is the lane's
@@ -206,11 +211,13 @@ __device__ __forceinline__ void store_row_16(const float (&o)[PX], __amdgpu_buff
     if constexpr (PX >= 4) {
 #pragma unroll
         for (int j = 0; j < PX / 4; ++j) {
-            u32x2 v = {h[4 * j] | (h[4 * j + 1] << 16), h[4 * j + 2] | (h[4 * j + 3] << 16)};
+            u32x2 v;
+            if constexpr (BF) v = u32x2{to_bf16_pair(o[4 * j], o[4 * j + 1]), to_bf16_pair(o[4 * j + 2], o[4 * j + 3])};
+            else v = u32x2{h[4 * j] | (h[4 * j + 1] << 16), h[4 * j + 2] | (h[4 * j + 3] << 16)};
             __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff + 8 * j, 0, HARRIS_STORE_AUX);
         }
     } else if constexpr (PX == 2) {
-        __builtin_amdgcn_raw_buffer_store_b32(h[0] | (h[1] << 16), rs, voff, 0, HARRIS_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b32(BF ? to_bf16_pair(o[0], o[1]) : h[0] | (h[1] << 16), rs, voff, 0, HARRIS_STORE_AUX);
     } else {
         __builtin_amdgcn_raw_buffer_store_b16((unsigned short)h[0], rs, voff, 0, HARRIS_STORE_AUX);
     }

@@ -568,6 +568,24 @@ def test_16_bit_results_layouts_and_overflow(gpu, oracle):
     clear = np.abs(np.abs(want32) - 65520) > 1e-4 * np.abs(want32).max()       # away from the overflow border
     assert np.array_equal(np.isinf(_as_f32(got, "f16"))[clear], np.isinf(_as_f32(wantb, "f16"))[clear])
     assert np.isinf(_as_f32(got, "f16")).any()
+    # infinities and NaN survive the conversion to either format: a NaN and an infinite sample
+    # in the image spoil the results around them, the rest stays finite
+    huge = big.copy()
+    huge[0, 1, 10, 20] = np.nan
+    huge[0, 0, 30, 200] = np.inf
+    src = torch.from_numpy(huge).cuda()
+    out32 = torch.empty((1, 36, 256), device="cuda")
+    gpu.harris_coarsity_typed(src, out32, K)
+    got32 = out32.cpu().numpy()
+    assert np.isnan(got32).any() and np.isfinite(got32).any()
+    for fmt, tdt in (("f16", torch.float16), ("bf16", torch.bfloat16)):
+        say("case %s of infinities and NaN" % fmt)
+        out16 = torch.empty((1, 36, 256), dtype=tdt, device="cuda")
+        gpu.harris_coarsity_typed(src, out16, K)
+        torch.cuda.synchronize()
+        g = _as_f32(out16.view(torch.int16).cpu().numpy().view(np.uint16), fmt)
+        w = _as_f32(oracle.round_to_16bit(got32, fmt), fmt)
+        assert np.array_equal(np.isnan(g), np.isnan(w)) and np.array_equal(g[~np.isnan(w)], w[~np.isnan(w)])
     # the band schedule has no 16-bit results
     with pytest.raises(gpu.HarrisError) as e:
         gpu.harris_coarsity_typed(torch.from_numpy(big).cuda(), out, K, tuning=dict(schedule=1))
