@@ -195,49 +195,51 @@ __device__ __forceinline__ uint32_t to_bf16_bits(float x) {
 }
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-// lo in bits 0..15, hi in bits 16..31
-__device__ __forceinline__ uint32_t to_bf16_pair(float lo, float hi) {
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+// Two values in one 32-bit word: lo in bits 0..15, hi in bits 16..31.
+template <bool BF>
+__device__ __forceinline__ uint32_t to_16bit_pair(float lo, float hi) {
     const f32x2 v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    if constexpr (BF) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
 
 // PX results of one lane as 16-bit values (BF: bfloat16, else binary16); voff is the lane's
 // byte offset in the row (2 bytes per column).
 template <int PX, bool BF>
 __device__ __forceinline__ void store_row_16(const float (&o)[PX], __amdgpu_buffer_rsrc_t rs, uint32_t voff) {
-    uint32_t h[PX];
-#pragma unroll
-    for (int i = 0; i < PX; ++i) h[i] = BF ? to_bf16_bits(o[i]) : to_f16_bits(o[i]);
     if constexpr (PX >= 4) {
 #pragma unroll
         for (int j = 0; j < PX / 4; ++j) {
-            u32x2 v;
-            if constexpr (BF) v = u32x2{to_bf16_pair(o[4 * j], o[4 * j + 1]), to_bf16_pair(o[4 * j + 2], o[4 * j + 3])};
-            else v = u32x2{h[4 * j] | (h[4 * j + 1] << 16), h[4 * j + 2] | (h[4 * j + 3] << 16)};
+            const u32x2 v = {to_16bit_pair<BF>(o[4 * j], o[4 * j + 1]), to_16bit_pair<BF>(o[4 * j + 2], o[4 * j + 3])};
             __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff + 8 * j, 0, HARRIS_STORE_AUX);
         }
     } else if constexpr (PX == 2) {
-        __builtin_amdgcn_raw_buffer_store_b32(BF ? to_bf16_pair(o[0], o[1]) : h[0] | (h[1] << 16), rs, voff, 0, HARRIS_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b32(to_16bit_pair<BF>(o[0], o[1]), rs, voff, 0, HARRIS_STORE_AUX);
     } else {
-        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)h[0], rs, voff, 0, HARRIS_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(BF ? to_bf16_bits(o[0]) : to_f16_bits(o[0])), rs, voff, 0, HARRIS_STORE_AUX);
     }
 }
 
-// PX results of one lane as 8-bit codes clamp(rint(fma(v, scale, offset)), 0, 255); NaN gives 0
-// (the maximum of NaN and 0 is 0).  voff is the lane's byte offset in the row (1 byte per column).
+// PX results of one lane as 8-bit codes clamp(rint(fma(v, scale, offset)), 0, 255); NaN gives 0.
+// The hardware's float-to-byte conversion does the rounding (to nearest, ties to even), the
+// clamp and the packing into byte i of a word in one instruction per value.  voff is the
+// lane's byte offset in the row (1 byte per column).
 template <int PX>
 __device__ __forceinline__ void store_row_8(const float (&o)[PX], float scale, float offset, __amdgpu_buffer_rsrc_t rs, uint32_t voff) {
-    uint32_t c[PX];
+    constexpr int WORDS = (PX + 3) / 4;
+    uint32_t w[WORDS];
 #pragma unroll
-    for (int i = 0; i < PX; ++i) c[i] = (uint32_t)fminf(fmaxf(rintf(fmaf(o[i], scale, offset)), 0.0f), 255.0f);
+    for (int j = 0; j < WORDS; ++j) w[j] = 0u;
+#pragma unroll
+    for (int i = 0; i < PX; ++i) w[i / 4] = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(o[i], scale, offset), (uint32_t)(i % 4), w[i / 4]);
     if constexpr (PX >= 4) {
 #pragma unroll
-        for (int j = 0; j < PX / 4; ++j)
-            __builtin_amdgcn_raw_buffer_store_b32(c[4 * j] | (c[4 * j + 1] << 8) | (c[4 * j + 2] << 16) | (c[4 * j + 3] << 24), rs, voff + 4 * j, 0, HARRIS_STORE_AUX);
+        for (int j = 0; j < WORDS; ++j) __builtin_amdgcn_raw_buffer_store_b32(w[j], rs, voff + 4 * j, 0, HARRIS_STORE_AUX);
     } else if constexpr (PX == 2) {
-        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(c[0] | (c[1] << 8)), rs, voff, 0, HARRIS_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)w[0], rs, voff, 0, HARRIS_STORE_AUX);
     } else {
-        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)c[0], rs, voff, 0, HARRIS_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)w[0], rs, voff, 0, HARRIS_STORE_AUX);
     }
 }
 

@@ -622,8 +622,25 @@ def test_8_bit_codes(gpu, oracle):
             rest = flat.clone()
             rest[off:off + B * n * pitch].view(B, n, pitch)[:, :, :m] = 77
             assert bool((rest == 77).all())
+    # Rounding itself: with a scale of 0 every code is the rounded, clamped offset (ties go to
+    # the even code, anything outside [0, 255] to the nearer end), and a NaN result gives 0.
+    rgb = hi.white_noise_f32(85, 1, 20, 264)
+    rgb[0, 2, 9, 100] = np.nan
+    src = torch.from_numpy(rgb).cuda()
+    codes = torch.empty((1, 16, 260), dtype=torch.uint8, device="cuda")
+    f32 = torch.empty((1, 16, 260), device="cuda")
+    gpu.harris_coarsity_typed(src, f32, K)
+    for q_offset, code in ((0.5, 0), (1.5, 2), (2.5, 2), (3.5, 4), (254.5, 254), (255.5, 255), (0.49999997, 0), (0.50000006, 1), (1.4999999, 1),
+                           (127.5, 128), (128.5, 128), (-0.5, 0), (-7.0, 0), (255.49998, 255), (300.0, 255), (1e30, 255), (-1e30, 0), (77.0, 77)):
+        say("case 8-bit code of %r" % q_offset)
+        gpu.harris_coarsity_quantized(src, codes, 0.0, q_offset)
+        torch.cuda.synchronize()
+        got = codes.cpu().numpy()
+        assert np.array_equal(got, oracle.quantize_u8(f32.cpu().numpy(), 0.0, q_offset))
+        nan = np.isnan(f32.cpu().numpy())
+        assert nan.any() and np.all(got[nan] == 0) and np.all(got[~nan] == code)
     with pytest.raises(gpu.HarrisError):
-        gpu.harris_coarsity_quantized(src, view, 1.0, 0.0, tuning=dict(schedule=1))
+        gpu.harris_coarsity_quantized(src, codes, 1.0, 0.0, tuning=dict(schedule=1))
 
 
 # ---------------------------------------------------------------- seeded random shapes, layouts and launch shapes
