@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files without comments, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "ff8563d2b3769a39808ce88ea4c29eff1ba4367459f5169b4df473f2d3326452"
-TRAFFIC_BYTES = {"noise_f32_1536x2560": 65140289, "rects_f32_64x1080x1920": 2199898589,
-                 "blobs_f32_2832x4256": 200194169, "noise_u8_8192x8192": 489677536}
+TRAFFIC_SOURCES_SHA256 = "e8732d7a2240b595524f87098bd4ef292872216b6be5354974a7d873d7ab3764"
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 65100173, "rects_f32_64x1080x1920": 2200089720,
+                 "blobs_f32_2832x4256": 200173760, "noise_u8_8192x8192": 489798486}
 
 
 def kernel_sources_sha256():
