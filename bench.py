@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files without comments, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "e8732d7a2240b595524f87098bd4ef292872216b6be5354974a7d873d7ab3764"
-TRAFFIC_BYTES = {"noise_f32_1536x2560": 65100173, "rects_f32_64x1080x1920": 2200089720,
-                 "blobs_f32_2832x4256": 200173760, "noise_u8_8192x8192": 489798486}
+TRAFFIC_SOURCES_SHA256 = "90f360e36b4894df0c74a7138a37fdb60f90fe835cd31ce1de9f88f696ed8891"
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 65098487, "rects_f32_64x1080x1920": 2156716288,
+                 "blobs_f32_2832x4256": 198548858, "noise_u8_8192x8192": 489834720}
 
 
 def kernel_sources_sha256():
@@ -66,6 +66,7 @@ def parse():
     ap.add_argument("--rows", type=int, default=0)
     ap.add_argument("--prefetch", type=int, default=0)
     ap.add_argument("--waves-per-block", type=int, default=0)
+    ap.add_argument("--lds-kb", type=int, default=0)
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-groupings", action="store_true", help="skip timing the unfused kernel groupings")
@@ -114,8 +115,8 @@ def main():
     ins = [base] + [torch.roll(base, shifts=i, dims=2) for i in range(1, n_pairs)]
     outs = [torch.empty((B, n, m), dtype=out_torch, device=dev) for _ in range(n_pairs)]
 
-    explicit_tuning = any((args.schedule, args.px, args.rows, args.prefetch, args.waves_per_block, args.flags))
-    tuning = pkg.HarrisTuning(args.schedule, args.px, args.rows, args.prefetch, args.waves_per_block, args.flags)
+    explicit_tuning = any((args.schedule, args.px, args.rows, args.prefetch, args.waves_per_block, args.flags, args.lds_kb))
+    tuning = pkg.HarrisTuning(args.schedule, args.px, args.rows, args.prefetch, args.waves_per_block, args.flags, args.lds_kb)
     shape, n_blocks = pkg.harris_plan_typed(pkg.HARRIS_U8 if is_u8 else pkg.HARRIS_F32, out_code, B, H, W, tuning=tuning)
     stream = torch.cuda.current_stream(dev)
     sptr = ctypes.c_void_p(stream.cuda_stream)

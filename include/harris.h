@@ -87,6 +87,12 @@ typedef enum harris_window {
  *   waves_per_block  BANDS: 1, 2 or 4 (2: two bands of a strip that start on shared rows;
  *             4: the same for two adjacent strips).  TILES: 2 to 16.  0 = default.
  *   flags     HARRIS_TUNE_* bits.
+ *   lds_kb    TILES only: kilobytes of LDS to reserve per workgroup, 0 to 64.  A tile needs 4 KB
+ *             per wavefront (px = 4); reserving more bounds the workgroups resident on a CU
+ *             (160 KB of LDS per CU: 64 -> 2, 48 -> 3, 36 -> 4, 28 -> 5).  Many-tile float32
+ *             launches are faster with 10 to 16 wavefronts per CU in flight than with the 28 to
+ *             32 that the registers would allow.  0 = chosen from the size (plans report the
+ *             reservation in force, at least the tile's own need).
  */
 typedef struct harris_tuning {
     int schedule;
@@ -95,6 +101,7 @@ typedef struct harris_tuning {
     int prefetch;
     int waves_per_block;
     unsigned flags;
+    int lds_kb;
 } harris_tuning;
 
 #define HARRIS_SCHEDULE_BANDS 1

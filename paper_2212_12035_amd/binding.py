@@ -44,7 +44,7 @@ class HarrisLayout(ctypes.Structure):
 class HarrisTuning(ctypes.Structure):
     """Mirror of `harris_tuning`."""
     _fields_ = [("schedule", ctypes.c_int), ("px", ctypes.c_int), ("rows", ctypes.c_int), ("prefetch", ctypes.c_int),
-                ("waves_per_block", ctypes.c_int), ("flags", ctypes.c_uint)]
+                ("waves_per_block", ctypes.c_int), ("flags", ctypes.c_uint), ("lds_kb", ctypes.c_int)]
 
     def as_dict(self):
         return {name: int(getattr(self, name)) for name, _ in self._fields_}

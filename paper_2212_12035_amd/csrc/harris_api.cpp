@@ -48,7 +48,7 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     if (W > (1 << 28)) return HARRIS_ERR_SHAPE;      // byte offsets within a row are 32-bit
     if (H > (1 << 30)) return HARRIS_ERR_SHAPE;      // row indices plus a tile's height stay within int
     if (rgb_align < 1 || out_align < out_elem_size(out_dtype)) return HARRIS_ERR_ARG;
-    harris_tuning t = {0, 0, 0, 0, 0, 0u};
+    harris_tuning t = {0, 0, 0, 0, 0, 0u, 0};
     if (tuning) t = *tuning;
     if (t.flags & ~(HARRIS_TUNE_NO_ALTERNATE | HARRIS_TUNE_NO_XCD_REMAP | HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS |
                     HARRIS_TUNE_ALIGNED_STORES | HARRIS_TUNE_PLAIN_STORES | HARRIS_TUNE_KEEP_SHARED_ROWS | HARRIS_TUNE_FLAG_HANDOFF)) return HARRIS_ERR_ARG;
@@ -69,7 +69,7 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
                  (px_fits(t.px, dtype, out_dtype, W, rgb_align, out_align) || (t.px == 4 && word_aligned_px4)))) {
         return HARRIS_ERR_ARG;
     }
-    if (t.rows < 0 || t.prefetch < 0 || t.waves_per_block < 0) return HARRIS_ERR_ARG;
+    if (t.rows < 0 || t.prefetch < 0 || t.waves_per_block < 0 || t.lds_kb < 0 || t.lds_kb > 64) return HARRIS_ERR_ARG;
     // px = 8 and a prefetch depth exist only in the band schedule.
     if (t.schedule == 0) t.schedule = t.px <= 4 && t.prefetch == 0 ? HARRIS_SCHEDULE_TILES : HARRIS_SCHEDULE_BANDS;
     if (out_dtype != HARRIS_OUT_F32 && t.schedule != HARRIS_SCHEDULE_TILES) return HARRIS_ERR_ARG;   // 16- and 8-bit results: tile kernel only
@@ -116,7 +116,8 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     // with 5 x 14; but 2160x3840 22.6 us with 10 x 14 against 24.1 us with 9 x 16).
     // Larger problems take many small tiles, which keep the memory system busiest (measured
     // on 2832x4256, 64x1080x1920 and 8192x8192 uint8).
-    int tile_rw = 4, tile_nw = 4;
+    int tile_rw = 4, tile_nw = 4, tile_lds_kb = 0;
+    bool one_per_cu = false;
     if (footprint <= (128LL << 20) && t.px == 4 && batch > 0 && n_strips > 0 && (long long)batch * n_strips <= 256) {
         const long long max_bands = 256 / ((long long)batch * n_strips);
         const long long need = (n + max_bands - 1) / max_bands + 4;         // input rows per tile
@@ -141,26 +142,40 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
             if (nw < 2) nw = 2;
             if (nw > 16) continue;
             const long long cost = nw * rw + (*list)[1];
-            if (best < 0 || cost < best) { best = cost; tile_rw = rw; tile_nw = (int)nw; }
+            if (best < 0 || cost < best) { best = cost; tile_rw = rw; tile_nw = (int)nw; one_per_cu = true; }
         }
-    } else if (tile4 && dtype == HARRIS_F32) {
-        // Many tiles of float32 input, measured against 4 x 4 (which stays for 8-bit input, where
-        // every taller tile is slower): one image of 128 to 400 MB, 4 wavefronts x 5 rows
-        // (2832x4256 34.0 against 35.3 us, 4096x4096 46.0 / 48.7, 3000x4000 34.4 / 34.6; several
-        // images of that total size gain nothing); above 400 MB 5 wavefronts x 6 rows up to 1 GB
-        // (4320x7680 97.1 against 105.2 us, 16x1080x1920 98.2 / 102.4, 6x2160x3840 139.7 / 146.0)
-        // and 5 x 8 beyond (32x1080x1920 184.2 / 193.9, 64x1080x1920 374.4 / 380.5, 8192x8192
-        // 182.7 / 181.8, 128x720x1280 334.4 / 332.8), all with the shared rows kept in cache.
-        // (16-bit results beyond 1 GB: 4 x 4, all loads with the default policy; 64x1080x1920 to
-        // binary16 345 us against 349 us with 5 x 6 and 353 us with 5 x 8.)
-        if (footprint > (1LL << 30)) { if (out_dtype == HARRIS_OUT_F32) { tile_rw = 8; tile_nw = 5; } }
-        else if (footprint > (400LL << 20)) { tile_rw = 6; tile_nw = 5; }
-        else if (footprint > (128LL << 20) && batch == 1) { tile_rw = 5; tile_nw = 4; }
+    }
+    if (!one_per_cu && tile4 && dtype == HARRIS_F32) {
+        // Many tiles of float32 input.  Such launches are fastest with 10 to 16 wavefronts in
+        // flight per CU, not with the 28 to 32 the registers allow (every wavefront requests all
+        // its rows at once; with fewer in flight the requests stay within what L2 and the memory
+        // controllers handle well), so the planner reserves LDS to hold the resident tiles down:
+        // 36 KB -> 4 tiles per CU, 48 KB -> 3, 64 KB -> 2.  Measured (shape x reservation swept
+        // together; 4 x 4 rows without reservation in brackets):
+        //   float32 results, up to 400 MB: 4 wavefronts x 5 rows, 3 per CU (2832x4256 32.7 [34.8]
+        //     us, 2x2160x3840 44.5 [49.1], 8192x8192 at 1 GB 174.6 [191.6]);
+        //   beyond, 8 images or more: 5 x 5, 2 per CU (16x1080x1920 87.1 [103.7] us, 64x1080x1920
+        //     351 [378], 128x720x1280 318 [350]); fewer, larger images: 5 x 6, 2 per CU
+        //     (4320x7680 92.2 [105.7] us, 8192x8192 176.6);
+        //   16-bit results and 8-bit codes above 128 MB: 4 x 6, 3 per CU (2832x4256 to binary16
+        //     29.1 [31.2] us, 16x1080x1920 75.7 [89.7], 64x1080x1920 331 [355], 4320x7680 80.8
+        //     [94.2]); one image beyond 800 MB: 5 x 6, 2 per CU (8192x8192 161 [184] us, 175
+        //     with 4 x 6);
+        //   up to 128 MB (several images, too many tiles for one per CU): 4 x 4, 4 per CU
+        //     (32x512x512 24.9 [25.6] us).
+        // 8-bit input is the opposite: every reservation costs time (8192x8192 uint8: 93 us with
+        // none, 102 us with 4 tiles per CU), so it keeps 4 x 4 and all the wavefronts that fit.
+        if (footprint <= (128LL << 20)) { tile_rw = 4; tile_nw = 4; tile_lds_kb = 36; }
+        else if (out_dtype != HARRIS_OUT_F32 && batch == 1 && footprint > (800LL << 20)) { tile_rw = 6; tile_nw = 5; tile_lds_kb = 64; }
+        else if (out_dtype != HARRIS_OUT_F32) { tile_rw = 6; tile_nw = 4; tile_lds_kb = 48; }
+        else if (footprint <= (400LL << 20)) { tile_rw = 5; tile_nw = 4; tile_lds_kb = 48; }
+        else if (batch >= 8) { tile_rw = 5; tile_nw = 5; tile_lds_kb = 64; }
+        else { tile_rw = 6; tile_nw = 5; tile_lds_kb = 64; }
     }
 
     long long tile_rows;       // result rows per band or tile
     if (t.schedule == HARRIS_SCHEDULE_TILES) {
-        if (t.rows == 0 && t.waves_per_block == 0) { t.rows = tile_rw; t.waves_per_block = tile_nw; }
+        if (t.rows == 0 && t.waves_per_block == 0) { t.rows = tile_rw; t.waves_per_block = tile_nw; if (t.lds_kb == 0) t.lds_kb = tile_lds_kb; }
         if (t.rows == 0) t.rows = 4;
         if (t.waves_per_block == 0) t.waves_per_block = 4;
         const bool rows_ok = t.rows == 4 || t.rows == 8 || (t.px == 4 && (t.rows == 5 || t.rows == 6 || t.rows == 9 || t.rows == 10));
@@ -170,7 +185,11 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
         if (t.prefetch != 0) return HARRIS_ERR_ARG;
         if (t.px > 4) return HARRIS_ERR_ARG;                           // 8 rows of 8 pixels per lane do not fit the registers
         tile_rows = (long long)t.rows * t.waves_per_block - 4;
+        // The reservation in force: at least the four gray rows each wavefront publishes.
+        const int need_kb = (int)(((long long)t.waves_per_block * 4 * 64 * t.px * 4 + 1023) / 1024);
+        if (t.lds_kb < need_kb) t.lds_kb = need_kb;
     } else {
+        if (t.lds_kb != 0) return HARRIS_ERR_ARG;                       // the band schedule uses no LDS
         const bool large = footprint > (256LL << 20);
         if (t.prefetch == 0) t.prefetch = large ? 6 : 3;
         if (!(t.prefetch == 2 || t.prefetch == 3 || t.prefetch == 6)) return HARRIS_ERR_ARG;
@@ -208,7 +227,6 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     const bool one_tile_per_cu = t.schedule == HARRIS_SCHEDULE_TILES && n_tiles <= 256;
     if (!(t.flags & (HARRIS_TUNE_CACHED_LOADS | HARRIS_TUNE_STREAM_LOADS))) {
         if (t.flags & HARRIS_TUNE_FLAG_HANDOFF) t.flags |= HARRIS_TUNE_STREAM_LOADS;
-        else if (dtype == HARRIS_F32 && out_dtype != HARRIS_OUT_F32 && footprint > (1LL << 30)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
         else if (tile4 && !one_tile_per_cu) t.flags |= HARRIS_TUNE_STREAM_LOADS | HARRIS_TUNE_KEEP_SHARED_ROWS;
         else if (dtype == HARRIS_F32 && footprint > (128LL << 20)) t.flags |= HARRIS_TUNE_CACHED_LOADS;
         else t.flags |= HARRIS_TUNE_STREAM_LOADS;
@@ -245,6 +263,7 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
         params->flags = t.flags;
         params->out_kind = (unsigned)out_dtype;
         params->in_shifted = in_shifted ? 1 : 0;
+        params->lds_bytes = (unsigned)t.lds_kb * 1024u;
     }
     return HARRIS_OK;
 }

@@ -108,8 +108,15 @@ int launch_copy_probe(const void* rgb, int dtype, int batch, int H, int W, float
     if (blocks > 0x7fffffffULL || batch > 65535) return HARRIS_ERR_SHAPE;
     const dim3 grid((unsigned)blocks, (unsigned)batch), block(256);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (dtype == HARRIS_U8) hipLaunchKernelGGL(copy_probe_u8, grid, block, 0, s, static_cast<const uint8_t*>(rgb), out, count, plane, chunks);
-    else hipLaunchKernelGGL((copy_probe_f32<2>), grid, block, 0, s, static_cast<const float*>(rgb), out, count, plane, chunks);
+    // Like the Harris tiles, large float32 copies are faster with fewer workgroups resident on
+    // a CU than would fit; LDS that nobody uses is reserved to hold them down (measured:
+    // 64x1080x1920 331 us with 2 workgroups per CU against 355 us with all that fit;
+    // 16x1080x1920 83.6 / 85.8 us; 2832x4256 31.1 / 31.3 us; 8192x8192 uint8 75.1 / 77.3 us), so
+    // that the probe stays the best plain copy known here.
+    const unsigned long long bytes = (unsigned long long)batch * count * (dtype == HARRIS_U8 ? 7 : 16);
+    const unsigned reserve = dtype == HARRIS_U8 ? 16u << 10 : bytes > (1ULL << 30) ? 64u << 10 : bytes > (400ULL << 20) ? 52u << 10 : bytes > (128ULL << 20) ? 36u << 10 : 0u;
+    if (dtype == HARRIS_U8) hipLaunchKernelGGL(copy_probe_u8, grid, block, reserve, s, static_cast<const uint8_t*>(rgb), out, count, plane, chunks);
+    else hipLaunchKernelGGL((copy_probe_f32<2>), grid, block, reserve, s, static_cast<const float*>(rgb), out, count, plane, chunks);
     return hipGetLastError() == hipSuccess ? HARRIS_OK : HARRIS_ERR_LAUNCH;
 }
 

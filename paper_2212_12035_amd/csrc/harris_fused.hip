@@ -688,7 +688,10 @@ hipError_t launch_bands(const harris_launch::Params& p, dim3 grid, dim3 block, h
 
 template <typename In, int PX, int RW>
 hipError_t launch_tiles(const harris_launch::Params& p, dim3 grid, dim3 block, hipStream_t stream) {
-    const size_t lds = (size_t)(block.x / kWave) * 4 * kWave * PX * sizeof(float);
+    // The four gray rows each wavefront publishes; the planner may reserve more to bound the
+    // number of workgroups resident on a CU.
+    const size_t lds_needed = (size_t)(block.x / kWave) * 4 * kWave * PX * sizeof(float);
+    const size_t lds = p.lds_bytes > lds_needed ? p.lds_bytes : lds_needed;
     const bool cached = p.flags & HARRIS_TUNE_CACHED_LOADS;
     if (p.in_shifted) {
         // 8-bit rows on any byte: kernels for 4 and 8 rows per wavefront, barrier hand-over.

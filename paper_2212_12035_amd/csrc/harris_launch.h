@@ -65,6 +65,7 @@ struct Params {
     unsigned out_kind;      // a harris_out_dtype (other than float32: tile kernel only)
     float q_scale, q_offset;   // 8-bit results: code = clamp(rint(fma(v, q_scale, q_offset)), 0, 255)
     int binomial;           // 1: window [1 2 1; 2 4 2; 1 2 1], 0: unweighted 3x3 sum
+    unsigned lds_bytes;     // TILES: dynamic LDS per workgroup (the tile's rows, or more to bound the resident workgroups)
     int in_shifted;         // 1: 8-bit rows that start on any byte, loaded as aligned words and shifted (tile kernel, px 4)
     unsigned n_bands;       // bands (BANDS) or tiles down the image (TILES)
     unsigned blocks_x;      // BANDS: workgroups across a row of bands

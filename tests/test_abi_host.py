@@ -74,18 +74,18 @@ def test_plan_tile_arithmetic(pkg):
     # bands of 16 -> 96 bands; 4 wavefronts per workgroup.
     t = dict(schedule=pkg.HARRIS_SCHEDULE_BANDS, px=4, rows=16, prefetch=3, waves_per_block=4, flags=pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES)
     shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=t)
-    assert shape == t and blocks == 6 * 48          # 2 strips x 2 bands per workgroup: ceil(11/2) x ceil(96/2)
+    assert shape == dict(t, lds_kb=0) and blocks == 6 * 48          # 2 strips x 2 bands per workgroup: ceil(11/2) x ceil(96/2)
     shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 3, 9, 9, tuning=dict(schedule=1, px=1, rows=2, prefetch=2, waves_per_block=1, flags=3))
     assert blocks == 3 * 3 * 1
     # tiles: 8 wavefronts x 8 rows give 60 result rows per tile -> 26 tiles down, 11 across,
     # one workgroup each
     t = dict(schedule=pkg.HARRIS_SCHEDULE_TILES, px=4, rows=8, prefetch=0, waves_per_block=8, flags=pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES)
     shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=t)
-    assert shape == t and blocks == 26 * 11
+    assert shape == dict(t, lds_kb=32) and blocks == 26 * 11      # 8 wavefronts publish 4 KB each
     # strip borders moved to 64-byte boundaries: strips of at most 240 columns; 4252 columns
     # take 18 of them instead of 17, 2556 columns still 11
     aligned = dict(t, flags=pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES)
-    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=aligned) == (aligned, 26 * 11)
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=aligned) == (dict(aligned, lds_kb=32), 26 * 11)
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 4256, tuning=aligned)[1] == 26 * 18
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 4256, tuning=t)[1] == 26 * 17
     # empty results plan to zero workgroups
@@ -116,23 +116,35 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     assert pkg.harris_plan(pkg.HARRIS_U8, 1, 1080, 1920)[1] == 8 * 90
     several, blocks = pkg.harris_plan(pkg.HARRIS_F32, 4, 480, 640)
     assert (several["rows"], several["waves_per_block"]) == (4, 4) and blocks == 4 * 3 * 40
-    # beyond one tile per CU: many tiles, non-temporal loads except the rows two tiles share, which stay in L2.
-    # One float32 image of 128 to 400 MB: 4 wavefronts x 5 rows (16 result rows per tile)
+    # beyond one tile per CU: many tiles, non-temporal loads except the rows two tiles share, which stay in L2,
+    # and an LDS reservation that holds the tiles resident on a CU down (160 KB per CU).
+    # float32 results of 128 to 400 MB: 4 wavefronts x 5 rows (16 result rows per tile), 3 tiles per CU
     mid, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4256)
-    assert (mid["schedule"], mid["rows"], mid["waves_per_block"]) == (2, 5, 4) and blocks == 18 * 177
+    assert (mid["schedule"], mid["rows"], mid["waves_per_block"], mid["lds_kb"]) == (2, 5, 4, 48) and blocks == 18 * 177
     assert mid["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_ALIGNED_STORES
-    assert [pkg.harris_plan(pkg.HARRIS_F32, 2, 2160, 3840)[0][key] for key in ("rows", "waves_per_block")] == [4, 4]
-    # 400 MB to 1 GB: 5 wavefronts x 6 rows; beyond: 5 x 8 (36 result rows per tile)
-    assert [pkg.harris_plan(pkg.HARRIS_F32, 16, 1080, 1920)[0][key] for key in ("rows", "waves_per_block")] == [6, 5]
+    assert [pkg.harris_plan(pkg.HARRIS_F32, 2, 2160, 3840)[0][key] for key in ("rows", "waves_per_block", "lds_kb")] == [5, 4, 48]
+    # beyond 400 MB: 8 images or more 5 wavefronts x 5 rows (21 result rows per tile), fewer images 5 x 6; 2 tiles per CU
+    assert [pkg.harris_plan(pkg.HARRIS_F32, 16, 1080, 1920)[0][key] for key in ("rows", "waves_per_block", "lds_kb")] == [5, 5, 64]
+    assert [pkg.harris_plan(pkg.HARRIS_F32, 1, 8192, 8192)[0][key] for key in ("rows", "waves_per_block", "lds_kb")] == [6, 5, 64]
     big, blocks = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920)
-    assert (big["rows"], big["waves_per_block"]) == (8, 5) and blocks == 64 * 30 * 8
+    assert (big["rows"], big["waves_per_block"], big["lds_kb"]) == (5, 5, 64) and blocks == 64 * 52 * 8
     assert big["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_ALIGNED_STORES
-    # 16-bit results beyond 1 GB: small tiles, every load with the default policy
+    # 16-bit results above 128 MB: 4 x 6, 3 tiles per CU; one image beyond 800 MB: 5 x 6, 2 per CU
     half, _ = pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_F16, 64, 1080, 1920)
-    assert (half["rows"], half["waves_per_block"]) == (4, 4) and half["flags"] == pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_ALIGNED_STORES
+    assert (half["rows"], half["waves_per_block"], half["lds_kb"]) == (6, 4, 48)
+    assert half["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_ALIGNED_STORES
+    wide, _ = pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_BF16, 1, 8192, 8192)
+    assert (wide["rows"], wide["waves_per_block"], wide["lds_kb"]) == (6, 5, 64)
+    # an explicit shape gets no reservation beyond the tile's own rows (4 KB per wavefront); an explicit one is kept
+    assert pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920, tuning=dict(rows=5, waves_per_block=5))[0]["lds_kb"] == 20
+    assert pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920, tuning=dict(rows=5, waves_per_block=5, lds_kb=40))[0]["lds_kb"] == 40
+    assert pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920, tuning=dict(lds_kb=28))[0]["lds_kb"] == 28
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)[0]["lds_kb"] == 36            # one tile per CU: 9 wavefronts, no more
+    # 8-bit input takes every wavefront that fits
+    assert pkg.harris_plan(pkg.HARRIS_U8, 1, 8192, 8192)[0]["lds_kb"] == 16
     # many tiles below 128 MB as well (32 images of 512x512 cannot be one tile per CU): shared rows kept
     many, blocks = pkg.harris_plan(pkg.HARRIS_F32, 32, 512, 512)
-    assert (many["rows"], many["waves_per_block"]) == (4, 4) and blocks > 256
+    assert (many["rows"], many["waves_per_block"], many["lds_kb"]) == (4, 4, 36) and blocks > 256
     assert many["flags"] == pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_KEEP_SHARED_ROWS | pkg.HARRIS_TUNE_ALIGNED_STORES
     # lanes narrower than 16 bytes have no mixed policy: default-policy loads from 128 MB on
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 2832, 4258, tuning=dict(px=2))[0]["flags"] == pkg.HARRIS_TUNE_CACHED_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES
@@ -171,7 +183,7 @@ def test_plan_rejects_bad_arguments(pkg):
     for bad in (dict(px=3), dict(px=4, prefetch=5), dict(schedule=1, px=4, waves_per_block=3), dict(waves_per_block=1), dict(flags=256), dict(flags=12), dict(flags=48), dict(flags=64), dict(flags=64 | 4), dict(schedule=1, flags=64 | 8), dict(px=2, flags=64 | 8),
                 dict(flags=128 | 4), dict(flags=128 | 64 | 8), dict(schedule=1, flags=128), dict(px=2, flags=128), dict(schedule=1, flags=16), dict(px=2, flags=16), dict(rows=-1),
                 dict(schedule=3), dict(schedule=2, rows=7), dict(schedule=2, px=2, rows=5), dict(schedule=2, waves_per_block=1), dict(schedule=2, waves_per_block=17),
-                dict(schedule=2, prefetch=3), dict(schedule=2, px=8)):
+                dict(schedule=2, prefetch=3), dict(schedule=2, px=8), dict(lds_kb=65), dict(lds_kb=-1), dict(schedule=1, lds_kb=16)):
         with pytest.raises(E) as e:
             pkg.harris_plan(0, 1, 64, 64, tuning=bad)
         assert e.value.status == -3
@@ -185,7 +197,7 @@ def test_plan_for_16_bit_results(pkg):
     F16, BF16 = pkg.HARRIS_OUT_F16, pkg.HARRIS_OUT_BF16
     shape, blocks = pkg.harris_plan_typed(pkg.HARRIS_F32, F16, 64, 1080, 1920)
     assert shape["schedule"] == pkg.HARRIS_SCHEDULE_TILES and shape["px"] == 4 and shape["flags"] & pkg.HARRIS_TUNE_ALIGNED_STORES
-    assert blocks == 64 * 90 * 9                                # ceil(1916 / 224) = 9 strips (8 for float32 results)
+    assert blocks == 64 * 54 * 9                                # ceil(1916 / 224) = 9 strips (8 for float32 results); tiles of 20 result rows
     # small problems and 8-bit input keep the wider strips with fixed borders
     small, blocks = pkg.harris_plan_typed(pkg.HARRIS_F32, F16, 1, 1536, 2560)
     assert small["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES and (small["rows"], small["waves_per_block"]) == (8, 9) and blocks == 253
@@ -201,8 +213,8 @@ def test_plan_for_16_bit_results(pkg):
         assert e.value.status == -3
     # 8-bit results: plain strips by default, at most 192 columns with moved borders, byte-aligned rows allowed
     u8out, blocks = pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_U8, 64, 1080, 1920)
-    assert u8out["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES and blocks == 64 * 90 * 8
-    assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_U8, 64, 1080, 1920, tuning=dict(flags=pkg.HARRIS_TUNE_ALIGNED_STORES))[1] == 64 * 90 * 10
+    assert u8out["flags"] & pkg.HARRIS_TUNE_PLAIN_STORES and blocks == 64 * 54 * 8
+    assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_U8, 64, 1080, 1920, tuning=dict(flags=pkg.HARRIS_TUNE_ALIGNED_STORES))[1] == 64 * 54 * 10
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_U8, 1, 64, 96, out_align=1)[0]["px"] == 1
     lib = pkg.load_library()
     one = ctypes.c_void_p(4096)

@@ -221,6 +221,29 @@ def test_tile_schedule_shapes(gpu, oracle):
         check(run_gpu(gpu, rgb, k=K, tuning=dict(schedule=2)), oracle.harris(rgb, K))
 
 
+def test_lds_reservation_changes_nothing_but_the_residency(gpu, oracle):
+    # Reserving more LDS than a tile needs only bounds the workgroups resident on a CU: the
+    # results are the same bit for bit, for every reservation the planner uses and the extremes.
+    import torch
+    rgb = hi.rectangles_f32(230, 3, 150, 1000)
+    want = oracle.harris(rgb, K)
+    src = torch.from_numpy(rgb).cuda()
+    for rows, waves in ((4, 4), (5, 4), (5, 5), (6, 5), (6, 4), (8, 9)):
+        base = None
+        for lds_kb in (0, 28, 36, 48, 64):
+            say("case tile %dx%d with %d KB of LDS reserved" % (waves, rows, lds_kb))
+            out = gpu.harris_coarsity_ex(src, K, tuning=dict(schedule=2, px=4, rows=rows, waves_per_block=waves, lds_kb=lds_kb))
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            check(got, want)
+            base = got if base is None else base
+            assert np.array_equal(got, base)
+    for bad in (dict(lds_kb=65), dict(lds_kb=-1), dict(schedule=1, lds_kb=16)):
+        with pytest.raises(gpu.HarrisError) as e:
+            gpu.harris_coarsity_ex(src, K, tuning=bad)
+        assert e.value.status == -3
+
+
 @pytest.mark.parametrize("px", [1, 2, 4, 8])
 @pytest.mark.parametrize("prefetch", [2, 3, 6])
 def test_u8_every_kernel_instance(gpu, oracle, px, prefetch):
