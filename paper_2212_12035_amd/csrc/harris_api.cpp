@@ -9,7 +9,7 @@
 
 namespace {
 
-constexpr int kVersion = 310;   // 0.3.1
+constexpr int kVersion = 320;   // 0.3.2
 
 bool power_of_two_aligned(uintptr_t p, unsigned bytes) { return (p & (uintptr_t)(bytes - 1)) == 0; }
 
