@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files without comments, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "90f360e36b4894df0c74a7138a37fdb60f90fe835cd31ce1de9f88f696ed8891"
-TRAFFIC_BYTES = {"noise_f32_1536x2560": 65098487, "rects_f32_64x1080x1920": 2156716288,
-                 "blobs_f32_2832x4256": 198548858, "noise_u8_8192x8192": 489834720}
+TRAFFIC_SOURCES_SHA256 = "b9cf52571b83e0c2ffb142e949a029691f9b4a918598fe522f3face71b7ede63"
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 65099586, "rects_f32_64x1080x1920": 2156397957,
+                 "blobs_f32_2832x4256": 198545208, "noise_u8_8192x8192": 489758915}
 
 
 def kernel_sources_sha256():
