@@ -813,8 +813,8 @@ def test_runs_on_a_side_stream(gpu, oracle):
 
 def test_captured_in_a_graph_and_replayed(gpu, oracle):
     # The library allocates nothing and never synchronises, so its launches can be captured.
-    # A graph of three launches (barrier hand-over, ready flags, 8-bit input through the shifted
-    # loads) is replayed several times with fresh inputs and eager work in between; every
+    # A graph of three launches (barrier hand-over, ready flags with 64 KB of LDS reserved, 8-bit
+    # input through the shifted loads) is replayed several times with fresh inputs and eager work in between; every
     # replay is checked against the oracle and against the eager launch, bit for bit.
     import torch
     H, W = 150, 1000
@@ -823,7 +823,7 @@ def test_captured_in_a_graph_and_replayed(gpu, oracle):
     out_a = torch.empty((1, H - 4, W - 4), device="cuda")
     out_f = torch.empty((1, H - 4, W - 4), device="cuda")
     out_b = torch.empty((1, H - 4, W - 5), device="cuda")
-    flags_tuning = dict(schedule=2, px=4, rows=8, waves_per_block=5, flags=gpu.HARRIS_TUNE_FLAG_HANDOFF)
+    flags_tuning = dict(schedule=2, px=4, rows=8, waves_per_block=5, flags=gpu.HARRIS_TUNE_FLAG_HANDOFF, lds_kb=64)
     a.copy_(torch.from_numpy(hi.white_noise_f32(400, 1, H, W)))
     b.copy_(torch.from_numpy(hi.white_noise_u8(401, 1, H, W - 1)))
     side = torch.cuda.Stream()
