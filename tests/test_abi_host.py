@@ -4,6 +4,7 @@ before anything is enqueued."""
 import ctypes
 import os
 import re
+import sys
 
 import pytest
 
@@ -330,3 +331,27 @@ def test_binding_refuses_host_tensors(pkg):
     import torch
     with pytest.raises(TypeError):
         pkg.harris_coarsity(torch.zeros(1, 3, 8, 8))
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    # The benchmark measures one GPU; asked for more it says so and exits before touching a device.
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr) and "{" not in r.stdout
+
+
+def test_traffic_figures_belong_to_the_kernels_in_the_tree():
+    # roofline.traffic is reported only while the kernel sources hash to the value recorded with
+    # the counters; after a change to the kernels the figure must be re-measured, not carried over.
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    assert set(bench.TRAFFIC_BYTES) == {"noise_f32_1536x2560", "rects_f32_64x1080x1920", "blobs_f32_2832x4256", "noise_u8_8192x8192"}
+    assert len(bench.TRAFFIC_SOURCES_SHA256) == 64 and len(bench.kernel_sources_sha256()) == 64
+    for name, traffic in bench.TRAFFIC_BYTES.items():
+        # measured HBM bytes lie between the algorithmic bytes and 1.15 times them
+        import harris_inputs
+        gen, seed, B, H, W, dt = harris_inputs.WORKLOADS[name]
+        algo = B * (3 * H * W * (1 if dt == "u8" else 4) + 4 * (H - 4) * (W - 4))
+        assert algo <= traffic <= 1.15 * algo, name
