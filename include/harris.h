@@ -176,9 +176,10 @@ typedef struct harris_layout {
 } harris_layout;
 
 /*
- * harris_coarsity_ex for pitched images.  layout == NULL means dense.  The widest lane
- * width is taken that the base pointers and all pitches allow (16-byte multiples for
- * the fastest path); `tuning` as in harris_coarsity_ex.
+ * harris_coarsity_ex for pitched images.  layout == NULL means dense.  Any pointers and
+ * pitches the element types allow run with four pixels per lane; rows that all start on
+ * 16-byte multiples (pointers and pitches, W % 4 == 0) also get moved strip borders
+ * (HARRIS_TUNE_ALIGNED_STORES), worth a few percent.  `tuning` as in harris_coarsity_ex.
  */
 int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
                             float k, float sobel_scale, int window, float* out,
@@ -203,7 +204,8 @@ typedef enum harris_out_dtype {
  *              with the pitches of `layout` counted in result elements; fully overwritten
  *   tuning     as in harris_coarsity_ex, but 16-bit results exist only in HARRIS_SCHEDULE_TILES
  *              (else HARRIS_ERR_ARG); with aligned stores their strips are at most 224 columns
- * The fastest path needs 8-byte aligned 16-bit result rows (pointer and pitches), W % 4 == 0.
+ * Four pixels per lane need 16-bit result rows on 4-byte boundaries (pointer and pitches);
+ * moved strip borders need them on 8-byte boundaries and W % 4 == 0.
  */
 int harris_coarsity_typed(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
                           float k, float sobel_scale, int window, void* out, int out_dtype,
