@@ -10,6 +10,12 @@ buffers, rotating over more than 1 GiB, so that no step finds its image in the
 Prints one JSON line: throughput in Mpixels/s (input pixels), the roofline object
 for the kernel (algorithmic bytes / launch duration against 8 TB/s of HBM) and the
 CPU oracle timed on this host as a baseline.
+
+Clocks.  After an idle period the GPU's clocks need about 10 ms of work to settle (the
+first several hundred launches of this size run some 5 % slower than the rest).  Whatever
+--warmup says, the timed region therefore starts only after at least SETTLE_MS of untimed
+back-to-back launches (their number is reported as config.settle_launches), so that a run
+of 20 timed steps measures the same steady state as one of 3000.
 """
 from __future__ import annotations
 
@@ -25,6 +31,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # published MI355X HBM3E bandwidth
+SETTLE_MS = 20.0               # untimed launches before the timed region, in GPU time
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files without comments, {workload: bytes}).
@@ -54,11 +61,10 @@ K_COARSITY = 0.04
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # Defaults: the GPU's clocks need about 10 ms of work after an idle period to settle (the
-    # first ~700 launches of this size run 5 % slower than the rest), so the untimed warm-up
-    # covers that; the timed region is then ~40 ms of back-to-back launches.
+    # Defaults: ~40 ms of back-to-back launches in the timed region.  The clocks are settled by
+    # time (SETTLE_MS), not by the warm-up count.
     ap.add_argument("--steps", type=int, default=3000)
-    ap.add_argument("--warmup", type=int, default=1500)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default=WORKLOAD, help="one of harris_inputs.WORKLOADS (default: the headline one)")
     ap.add_argument("--rotate-bytes", type=float, default=float(1 << 30), help="distinct buffer bytes to rotate over")
     ap.add_argument("--schedule", type=int, default=0, help="0 auto, 1 bands, 2 tiles")
@@ -88,8 +94,8 @@ def main():
     import paper_2212_12035_amd as pkg
 
     if not os.path.exists(pkg.library_path()):
-        import __graft_entry__
-        __graft_entry__.build()
+        from paper_2212_12035_amd import build as product_build
+        product_build.build_library()
     lib = pkg.load_library()
 
     gen, seed, B, H, W, dt = harris_inputs.WORKLOADS[args.workload]
@@ -138,6 +144,19 @@ def main():
         step(i)
     torch.cuda.synchronize(dev)
 
+    # Settle the clocks by time: a short probe gives the launch duration, then as many untimed
+    # back-to-back launches as fill SETTLE_MS, in one go (no gaps in which the clocks could fall
+    # again), and the timed region follows the synchronisation at once.
+    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s0.record(stream)
+    for i in range(40):
+        step(i)
+    s1.record(stream)
+    torch.cuda.synchronize(dev)
+    settle_launches = 40 + max(0, int(SETTLE_MS / max(s0.elapsed_time(s1) / 40, 1e-4)) + 1)
+    for i in range(settle_launches - 40):
+        step(i)
+
     # Timed region: exactly `steps` launches, wall clock between synchronisations, and a
     # pair of HIP events on the launch stream for the GPU-side duration.
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -153,6 +172,24 @@ def main():
     gpu_ms = ev0.elapsed_time(ev1)
     ms_per_step = wall_ms / args.steps
     launch_us = gpu_ms * 1e3 / args.steps                 # average per launch over the timed region
+
+    # The kernel's own duration, for the roofline: an event pair around further launches issued
+    # right behind a few untimed ones, with no synchronisation in between.  The pair of the timed
+    # region above starts on an idle queue, so it also contains the host's latency until the first
+    # launch arrives (some 5 to 10 us, which is 4 % of 20 steps and nothing of 3000); here the
+    # queue is busy when the first event is reached, and what the pair brackets is kernels back to
+    # back: the figure that rocprofv3's kernel trace gives for the same launches.
+    KERNEL_LEAD_IN = 12
+    n_kernel = max(args.steps, 200)
+    k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(KERNEL_LEAD_IN):
+        step(i)
+    k0.record(stream)
+    for i in range(n_kernel):
+        step(KERNEL_LEAD_IN + i)
+    k1.record(stream)
+    torch.cuda.synchronize(dev)
+    kernel_us = k0.elapsed_time(k1) * 1e3 / n_kernel
 
     # Single-launch durations (event pair around each launch), for information.
     pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(args.steps, 60))]
@@ -186,7 +223,7 @@ def main():
             g1.record(stream)
             torch.cuda.synchronize(dev)
             groupings["grouping_%d_us" % g] = round(g0.elapsed_time(g1) * 1e3 / reps, 2)
-        groupings["grouping_4_fused_us"] = round(launch_us, 2)
+        groupings["grouping_4_fused_us"] = round(kernel_us, 2)
         del ws
         step(0)                                   # pair 0 holds the fused kernel's result again
         torch.cuda.synchronize(dev)
@@ -219,7 +256,7 @@ def main():
     # Correctness of what was timed: pair 0 against the oracle (also the CPU baseline).
     got = outs[0].float().cpu().numpy()
     cpu = None
-    max_err = bound = None
+    max_err = bound = rounding = None
     if not args.no_cpu_baseline:
         from oracle import harris_oracle
         nt = harris_oracle.hardware_threads()
@@ -241,11 +278,21 @@ def main():
         elif args.out_dtype != "f32":              # plus one spacing of the 16-bit format at the largest value
             bound += float(np.abs(want).max()) * (2.0 ** -10 if args.out_dtype == "f16" else 2.0 ** -7)
         max_err = float(np.abs(got[:sample.shape[0]] - want).max())
+        if args.out_dtype == "f32":
+            # Beside the bar, a diagnostic at rounding level: the distance to the float64 referee in
+            # units of float32 eps times the largest trace^2 (every term of the coarsity is bounded
+            # by trace^2; a correct float32 implementation stays within a few units).
+            ref64 = harris_oracle.harris(sample, K_COARSITY, precision="f64", nthreads=nt)
+            unit = float(np.finfo(np.float32).eps) * harris_oracle.max_trace_squared(sample)
+            rounding = {"gpu_vs_f64_in_eps_trace2": round(float(np.abs(got[:sample.shape[0]] - ref64).max()) / unit, 3),
+                        "oracle_f32_vs_f64_in_eps_trace2": round(float(np.abs(want - ref64).max()) / unit, 3), "limit": 64.0}
         cpu = {"value": round(spx / ta[len(ta) // 2] / 1e6, 2), "unit": "Mpixels/s", "cores": nt, "kind": "oracle",
                "sample": "%d image(s) of %s: median of %d runs on %d threads (and of %d runs on one thread), about %.0f s of CPU work" % (sample.shape[0], args.workload, reps_all, nt, reps_one, sum(ta) * nt + sum(to)),
                "value_1_thread": round(spx / to[len(to) // 2] / 1e6, 2)}
 
-    achieved = algo_bytes / (launch_us * 1e-6) / 1e9
+    achieved = algo_bytes / (kernel_us * 1e-6) / 1e9
+    achieved_wall = algo_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved_region = algo_bytes / (launch_us * 1e-6) / 1e9
     result = {
         "metric": "harris_mpixels_per_s",
         "value": round(pixels / (ms_per_step * 1e-3) / 1e6, 1),
@@ -253,12 +300,21 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "batch": B, "H": H, "W": W, "input": dt, "k": K_COARSITY,
+        "dtype": "u8" if is_u8 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": B, "H": H, "W": W, "input": dt, "arithmetic": "f32", "k": K_COARSITY,
                    "result": args.out_dtype, "buffer_pairs": n_pairs, "cache": "warm" if args.warm_cache else "cold (rotating buffers)",
+                   "settle_launches": settle_launches, "settle_ms": SETTLE_MS,
                    "launch": shape, "workgroups": n_blocks},
+        # achieved/frac: algorithmic bytes over the kernel's average duration (event pair around
+        # kernel_launches back-to-back launches on a busy queue).  The same bytes over the two clocks
+        # of the timed region of `steps` launches are given beside it: its own event pair (which
+        # starts on an idle queue) and the wall clock between the synchronisations (`value`'s clock).
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "clock": "HIP event pair on the launch stream around kernel_launches launches behind %d untimed ones, no synchronisation in between" % KERNEL_LEAD_IN,
+                     "kernel_launches": n_kernel, "kernel_us_avg": round(kernel_us, 3),
+                     "achieved_timed_region_events": round(achieved_region, 1), "frac_timed_region_events": round(achieved_region / HBM_PEAK_GBS, 4),
+                     "achieved_wall": round(achieved_wall, 1), "frac_wall": round(achieved_wall / HBM_PEAK_GBS, 4),
                      "traffic": TRAFFIC_BYTES.get(args.workload) if kernel_sources_sha256() == TRAFFIC_SOURCES_SHA256 and not explicit_tuning and args.out_dtype == "f32" else None,
                      "algorithmic_bytes_per_launch": algo_bytes,
                      "launch_us_avg_over_timed_region": round(launch_us, 3),
@@ -267,11 +323,13 @@ def main():
         "copy_probe": probe,
         "cpu_baseline": cpu,
         "kernel_groupings": groupings,
-        "max_abs_err_vs_oracle": max_err, "err_bound": bound,
+        "max_abs_err_vs_oracle": max_err, "err_bound": bound, "rounding": rounding,
     }
     print(json.dumps(result))
     if max_err is not None and not max_err <= bound:
         sys.exit("bench: GPU result differs from the oracle by %g (bound %g)" % (max_err, bound))
+    if rounding is not None and not rounding["gpu_vs_f64_in_eps_trace2"] <= rounding["limit"]:
+        sys.exit("bench: GPU result is %g eps*trace^2 from the float64 referee (limit %g)" % (rounding["gpu_vs_f64_in_eps_trace2"], rounding["limit"]))
 
 
 if __name__ == "__main__":

@@ -64,73 +64,12 @@ typedef enum harris_window {
 } harris_window;
 
 /*
- * Optional launch shape, for benchmarking and tests.  Pass NULL (or zero fields)
- * to let the library choose.  Results never depend on it beyond rounding.
- *
- *   schedule  HARRIS_SCHEDULE_BANDS: one wavefront walks a band of `rows` result rows of
- *             one strip from top to bottom (or bottom to top), with `prefetch` input rows
- *             in flight.  HARRIS_SCHEDULE_TILES: a workgroup of `waves_per_block`
- *             wavefronts loads a tile of waves_per_block * rows input rows at once and
- *             hands the gray rows that two wavefronts share through LDS.  0 = chosen
- *             from the size.
- *   px        pixels per lane along x: 1, 2, 4 or (BANDS only) 8.  A lane's loads and stores
- *             must be naturally aligned in every row (px divides W, pointers and pitches are
- *             multiples of the access size), else HARRIS_ERR_ARG; except that TILES with px = 4
- *             takes any width and any row alignment the element type allows, as long as result
- *             rows start on 4-byte boundaries and are not 8-bit codes (vector accesses on 4-byte
- *             boundaries; 8-bit input rows on any byte are loaded as aligned words and
- *             shifted).  0 = 4 where that holds, else the widest of 2, 1 that fits.
- *   rows      BANDS: result rows per band (>= 1).  TILES: input rows per wavefront: 4 or 8,
- *             and with px = 4 also 5, 6, 9 or 10 (not for 8-bit input rows off 4-byte
- *             boundaries).  0 = chosen from the size.
- *   prefetch  BANDS only: input rows kept in flight per wavefront, 2, 3 or 6; 0 = default.
- *   waves_per_block  BANDS: 1, 2 or 4 (2: two bands of a strip that start on shared rows;
- *             4: the same for two adjacent strips).  TILES: 2 to 16.  0 = default.
- *   flags     HARRIS_TUNE_* bits.
- *   lds_kb    TILES only: kilobytes of LDS to reserve per workgroup, 0 to 64.  A tile needs 4 KB
- *             per wavefront (px = 4); reserving more bounds the workgroups resident on a CU
- *             (160 KB of LDS per CU: 64 -> 2, 48 -> 3, 36 -> 4, 28 -> 5).  Many-tile float32
- *             launches are faster with 10 to 16 wavefronts per CU in flight than with the 28 to
- *             32 that the registers would allow.  0 = chosen from the size (plans report the
- *             reservation in force, at least the tile's own need).
+ * Launch-shape override for benchmarks and tests; NULL in ordinary use (the library then
+ * chooses the shape from the problem).  The structure, its flag bits and the planning
+ * calls are declared in harris_tuning.h, which is not needed to use the operator.
+ * Results never depend on the launch shape beyond rounding.
  */
-typedef struct harris_tuning {
-    int schedule;
-    int px;
-    int rows;
-    int prefetch;
-    int waves_per_block;
-    unsigned flags;
-    int lds_kb;
-} harris_tuning;
-
-#define HARRIS_SCHEDULE_BANDS 1
-#define HARRIS_SCHEDULE_TILES 2
-
-#define HARRIS_TUNE_NO_ALTERNATE 1u  /* BANDS: all bands walk downwards (default: odd bands walk
-                                        upwards, so that neighbouring bands read their shared rows
-                                        at the same time)                                            */
-#define HARRIS_TUNE_NO_XCD_REMAP 2u  /* workgroup i takes tile group i (default: tiles are dealt so
-                                        that each of the 8 XCDs gets one contiguous run of tiles)   */
-#define HARRIS_TUNE_CACHED_LOADS 4u  /* load input rows with the default cache policy             */
-#define HARRIS_TUNE_STREAM_LOADS 8u  /* load input rows non-temporal.  With neither bit the library
-                                        decides from the size of the problem                        */
-#define HARRIS_TUNE_KEEP_SHARED_ROWS 64u /* TILES with px = 4 and non-temporal loads only: the input rows
-                                        that two vertically adjacent tiles both read (the first and the
-                                        last four of a tile) are loaded with the default policy instead,
-                                        so that the second reader finds them in L2                   */
-#define HARRIS_TUNE_FLAG_HANDOFF 128u /* TILES with px = 4, plain non-temporal loads and input rows on
-                                        4-byte boundaries only: a wavefront
-                                        waits for a ready flag of the wavefront below it instead of
-                                        the workgroup's barrier (and a barrier holds the stores back
-                                        until the workgroup's loads are in): for few, large tiles     */
-#define HARRIS_TUNE_ALIGNED_STORES 16u /* TILES with px = 4 and naturally aligned lanes only: in every result row the border between
-                                        two strips is moved right to the next 64-byte boundary of the
-                                        row's address, so that no 64-byte block of the result is
-                                        written by two wavefronts; strips are then at most 240
-                                        columns wide instead of 252                                 */
-#define HARRIS_TUNE_PLAIN_STORES 32u /* strips end at the same column in every row.  With neither bit
-                                        the library decides                                         */
+typedef struct harris_tuning harris_tuning;
 
 /*
  * Harris coarsity of float32 images with the integer Sobel matrices
@@ -154,7 +93,7 @@ int harris_coarsity_u8(const uint8_t* rgb, int batch, int H, int W, float k, flo
  *                listings (section 4.2), whose results are those of scale 1
  *                divided by 12^4.
  *   window       a harris_window
- *   tuning       NULL, or a launch shape (see harris_tuning)
+ *   tuning       NULL, or a launch shape (harris_tuning.h)
  */
 int harris_coarsity_ex(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale,
                        int window, float* out, const harris_tuning* tuning, void* stream);
@@ -168,7 +107,11 @@ int harris_coarsity_ex(const void* rgb, int dtype, int batch, int H, int W, floa
  * out[b*out_image_pitch + y*out_row_pitch + x] (in floats).  Requirements, else
  * HARRIS_ERR_SHAPE: rgb_row_pitch >= W, rgb_plane_pitch >= (H-1)*rgb_row_pitch + W,
  * rgb_image_pitch >= 2*rgb_plane_pitch + (H-1)*rgb_row_pitch + W, out_row_pitch >= W-4,
- * out_image_pitch >= (H-5)*out_row_pitch + W-4.  Padding is never read or written.
+ * out_image_pitch >= (H-5)*out_row_pitch + W-4.  Bytes outside the rows are never written.
+ * They are never read either, except that rows of uint8 input that do not start on 4-byte
+ * boundaries are loaded as the aligned 32-bit words that hold them: up to 3 bytes before a
+ * row's first and after its last element may be read (never beyond those words) and are
+ * discarded.
  */
 typedef struct harris_layout {
     long long rgb_row_pitch, rgb_plane_pitch, rgb_image_pitch;
@@ -179,7 +122,7 @@ typedef struct harris_layout {
  * harris_coarsity_ex for pitched images.  layout == NULL means dense.  Any pointers and
  * pitches the element types allow run with four pixels per lane; rows that all start on
  * 16-byte multiples (pointers and pitches, W % 4 == 0) also get moved strip borders
- * (HARRIS_TUNE_ALIGNED_STORES), worth a few percent.  `tuning` as in harris_coarsity_ex.
+ * (see harris_tuning.h), worth a few percent.  `tuning` as in harris_coarsity_ex.
  */
 int harris_coarsity_pitched(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
                             float k, float sobel_scale, int window, float* out,
@@ -202,10 +145,11 @@ typedef enum harris_out_dtype {
  * results stay below that; larger inputs may not).
  *   out        device, element type given by out_dtype (HARRIS_OUT_F32, _F16 or _BF16), [batch][H-4][W-4]
  *              with the pitches of `layout` counted in result elements; fully overwritten
- *   tuning     as in harris_coarsity_ex, but 16-bit results exist only in HARRIS_SCHEDULE_TILES
- *              (else HARRIS_ERR_ARG); with aligned stores their strips are at most 224 columns
- * Four pixels per lane need 16-bit result rows on 4-byte boundaries (pointer and pitches);
- * moved strip borders need them on 8-byte boundaries and W % 4 == 0.
+ *   tuning     as in harris_coarsity_ex, but 16-bit results exist only in the tile schedule
+ *              (else HARRIS_ERR_ARG)
+ * Four pixels per lane need 16-bit result rows that start on 4-byte boundaries (pointer and
+ * pitches) and an even W, so that no 32-bit word of a store holds the last column of a row
+ * together with something behind it; other shapes run with one pixel per lane.
  */
 int harris_coarsity_typed(const void* rgb, int dtype, int batch, int H, int W, const harris_layout* layout,
                           float k, float sobel_scale, int window, void* out, int out_dtype,
@@ -226,23 +170,10 @@ int harris_coarsity_quantized(const void* rgb, int dtype, int batch, int H, int 
                               uint8_t* out, const harris_tuning* tuning, void* stream);
 
 /*
- * The launch shape harris_coarsity_ex would use for this problem (after applying
- * `tuning`, which may be NULL), written to *chosen; also the number of workgroups
- * in *n_blocks if n_blocks is not NULL.  rgb_align / out_align are the byte
- * alignments of the base pointers (pass 16 for ordinary allocations).  Host only;
- * touches no device.  Returns a harris_status.
- */
-int harris_plan(int dtype, int batch, int H, int W, int rgb_align, int out_align,
-                const harris_tuning* tuning, harris_tuning* chosen, long long* n_blocks);
-
-/* The same for harris_coarsity_typed: out_dtype is a harris_out_dtype. */
-int harris_plan_typed(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int out_align,
-                      const harris_tuning* tuning, harris_tuning* chosen, long long* n_blocks);
-
-/*
  * The same result computed by several kernels that keep their intermediate images in
- * device memory: the kernel groupings of the thesis's section 3.5.3 (table "Four
- * different kernel groupings"), each preceded by a grayscale kernel.
+ * device memory: the kernel groupings of the thesis's chapter 3, section "Explicit Kernel
+ * Execution", subsection "Evaluating the Boilerplate Avoided through Kernel Execution"
+ * (table "Four different kernel groupings"), each preceded by a grayscale kernel.
  *   grouping 1  [Sx] [Sy] [x] [+] [coarsity], one kernel per operator and image (10 launches)
  *   grouping 2  [Sx, Sy, x] [+, coarsity]
  *   grouping 3  [Sx, Sy] [x, +, coarsity]
@@ -260,17 +191,6 @@ int harris_coarsity_grouped(const void* rgb, int dtype, int batch, int H, int W,
 
 /* Workspace bytes harris_coarsity_grouped needs; 0 for grouping 4; -1 for invalid arguments. Host only. */
 long long harris_grouped_workspace_bytes(int grouping, int batch, int H, int W);
-
-/*
- * Measurement aid, not the Harris operator: a plain streaming kernel with the traffic of one
- * Harris launch.  For every image it reads the first (H-4)*(W-4) elements of each of the three
- * planes (taken as flat arrays) and writes their sum as float32 to out[b][i]: 3*e + 4 bytes per
- * result pixel, e = 4 or 1, against the 3*e*H*W + 4*(H-4)*(W-4) of the operator.  Its duration
- * beside harris_coarsity's shows what this read/write mix reaches on the GPU at hand.
- * Requires dense arrays, 16-byte aligned rgb and out, H*W*e and (H-4)*(W-4)*4 multiples of 16,
- * batch <= 65535 (else HARRIS_ERR_ARG / HARRIS_ERR_SHAPE); arguments otherwise as harris_coarsity.
- */
-int harris_probe_copy(const void* rgb, int dtype, int batch, int H, int W, float* out, void* stream);
 
 /* Static, NUL-terminated description of a harris_status value. */
 const char* harris_strerror(int status);

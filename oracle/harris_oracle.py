@@ -179,3 +179,27 @@ def quantize_u8(values: np.ndarray, scale: float, offset: float) -> np.ndarray:
     out = np.empty(a.shape, dtype=np.uint8)
     _load().harris_ref_quantize_u8(_ptr(a), a.size, scale, offset, _ptr(out))
     return out
+
+
+def max_trace_squared(rgb: np.ndarray, sobel_scale: float = 1.0, window: int = 0) -> float:
+    """Largest (Sxx + Syy)^2 over all images of rgb[batch][3][H][W], from the float64 stages above.
+
+    Not a result anybody is checked against: the scale of the rounding diagnostic.  Every term of
+    the coarsity is bounded by trace^2, so float32 rounding of a correct implementation stays
+    within a few eps * trace^2, whatever the cancellation in det."""
+    a = rgb[None] if rgb.ndim == 3 else rgb
+    binomial = np.array([[1, 2, 1], [2, 4, 2], [1, 2, 1]], dtype=np.float64)
+    worst = 0.0
+    for img in a:
+        f = img.astype(np.float64)
+        if img.dtype == np.uint8:
+            f = f / 255.0
+        g = gray(f)
+        ix, iy = sobel(g, "x", sobel_scale), sobel(g, "y", sobel_scale)
+        if window == 0:
+            tr = sum3x3(mul(ix, ix)) + sum3x3(mul(iy, iy))
+        else:
+            tr = conv3x3(mul(ix, ix), binomial) + conv3x3(mul(iy, iy), binomial)
+        if tr.size:
+            worst = max(worst, float(tr.max()) ** 2)
+    return worst

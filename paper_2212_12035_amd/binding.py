@@ -1,4 +1,4 @@
-"""ctypes binding of libharris (include/harris.h): argument marshalling only.
+"""ctypes binding of libharris (include/harris.h, include/harris_tuning.h): argument marshalling only.
 
 The functions have the names and argument order of the C entry points.  Images
 are torch tensors on a ROCm device; their data pointers and the current HIP stream
@@ -19,7 +19,7 @@ HARRIS_TUNE_ALIGNED_STORES, HARRIS_TUNE_PLAIN_STORES, HARRIS_TUNE_KEEP_SHARED_RO
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libharris.so")
 
-#: every symbol include/harris.h declares
+#: every symbol include/harris.h and include/harris_tuning.h declare
 EXPORTS = ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan", "harris_plan_typed",
            "harris_coarsity_pitched", "harris_coarsity_typed", "harris_coarsity_quantized", "harris_coarsity_grouped",
            "harris_grouped_workspace_bytes", "harris_probe_copy", "harris_strerror", "harris_version")
@@ -65,7 +65,7 @@ def load_library() -> ctypes.CDLL:
     if not os.path.exists(_LIB_PATH):
         raise RuntimeError(
             "libharris.so is not built (expected at %s). Build it with "
-            "`python -c 'import __graft_entry__ as g; g.build()'` from the repository root. "
+            "`python -m paper_2212_12035_amd.build` from the repository root. "
             "There is no CPU fallback." % _LIB_PATH)
     lib = ctypes.CDLL(_LIB_PATH)
     vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
@@ -178,11 +178,10 @@ def harris_coarsity_ex(rgb, k: float = 0.04, sobel_scale: float = 1.0, window: i
     return out
 
 
-def harris_coarsity_pitched(rgb, out, k: float = 0.04, sobel_scale: float = 1.0, window: int = HARRIS_WINDOW_BOX,
-                            tuning=None, stream=None):
-    """General form for strided tensors: rgb [batch][3][H][W] and out [batch][H-4][W-4] may be views
-    (padded rows, a region of interest, a slice of planes) as long as the last stride is 1 and the
-    other strides are non-negative; the pitches are taken from the tensors' strides."""
+def _strided(rgb, out, out_dtypes, what):
+    """Checks of the entry points that take views; returns (B, H, W, layout, input dtype code).
+    rgb [batch][3][H][W] and out [batch][H-4][W-4] may be views (padded rows, a region of
+    interest, a slice of planes) as long as the last stride is 1; the pitches are the strides."""
     import torch
     if (not isinstance(rgb, torch.Tensor) or rgb.device.type != "cuda" or rgb.dtype not in (torch.float32, torch.uint8)
             or rgb.dim() != 4 or rgb.shape[1] != 3):
@@ -190,14 +189,21 @@ def harris_coarsity_pitched(rgb, out, k: float = 0.04, sobel_scale: float = 1.0,
     B, _, H, W = rgb.shape
     if H < 4 or W < 4:
         raise HarrisError(-2, harris_strerror(-2))
-    if (not isinstance(out, torch.Tensor) or out.device != rgb.device or out.dtype != torch.float32
+    if (not isinstance(out, torch.Tensor) or out.device != rgb.device or out.dtype not in out_dtypes
             or tuple(out.shape) != (B, H - 4, W - 4)):
-        raise ValueError("out must be a float32 tensor [batch][H-4][W-4] on rgb's device")
+        raise ValueError("out must be a %s tensor [batch][H-4][W-4] on rgb's device" % what)
     if (W > 1 and rgb.stride(3) != 1) or (W - 4 > 1 and out.stride(2) != 1):
         raise ValueError("the last dimension of rgb and out must have stride 1")
     lay = HarrisLayout(rgb.stride(2) if H > 1 else W, rgb.stride(1), rgb.stride(0) if B > 1 else 3 * rgb.stride(1),
                        out.stride(1) if H - 4 > 1 else max(W - 4, 1), out.stride(0) if B > 1 else max(1, (H - 4) * out.stride(1)))
-    dtype = HARRIS_U8 if rgb.dtype == torch.uint8 else HARRIS_F32
+    return B, H, W, lay, HARRIS_U8 if rgb.dtype == torch.uint8 else HARRIS_F32
+
+
+def harris_coarsity_pitched(rgb, out, k: float = 0.04, sobel_scale: float = 1.0, window: int = HARRIS_WINDOW_BOX,
+                            tuning=None, stream=None):
+    """General form for strided tensors (views); float32 result."""
+    import torch
+    B, H, W, lay, dtype = _strided(rgb, out, (torch.float32,), "float32")
     with torch.cuda.device(rgb.device):
         _check(load_library().harris_coarsity_pitched(rgb.data_ptr(), dtype, B, H, W, ctypes.byref(lay), k, sobel_scale, window,
                                                       out.data_ptr(), _tuning_arg(tuning), _stream_ptr(stream, rgb.device)))
@@ -209,20 +215,7 @@ def harris_coarsity_typed(rgb, out, k: float = 0.04, sobel_scale: float = 1.0, w
     """harris_coarsity_pitched with the result type taken from `out`: float32, float16 or bfloat16."""
     import torch
     kinds = {torch.float32: HARRIS_OUT_F32, torch.float16: HARRIS_OUT_F16, torch.bfloat16: HARRIS_OUT_BF16}
-    if (not isinstance(rgb, torch.Tensor) or rgb.device.type != "cuda" or rgb.dtype not in (torch.float32, torch.uint8)
-            or rgb.dim() != 4 or rgb.shape[1] != 3):
-        raise TypeError("rgb must be a float32 or uint8 ROCm tensor of shape [batch][3][H][W]")
-    B, _, H, W = rgb.shape
-    if H < 4 or W < 4:
-        raise HarrisError(-2, harris_strerror(-2))
-    if (not isinstance(out, torch.Tensor) or out.device != rgb.device or out.dtype not in kinds
-            or tuple(out.shape) != (B, H - 4, W - 4)):
-        raise ValueError("out must be a float32, float16 or bfloat16 tensor [batch][H-4][W-4] on rgb's device")
-    if (W > 1 and rgb.stride(3) != 1) or (W - 4 > 1 and out.stride(2) != 1):
-        raise ValueError("the last dimension of rgb and out must have stride 1")
-    lay = HarrisLayout(rgb.stride(2) if H > 1 else W, rgb.stride(1), rgb.stride(0) if B > 1 else 3 * rgb.stride(1),
-                       out.stride(1) if H - 4 > 1 else max(W - 4, 1), out.stride(0) if B > 1 else max(1, (H - 4) * out.stride(1)))
-    dtype = HARRIS_U8 if rgb.dtype == torch.uint8 else HARRIS_F32
+    B, H, W, lay, dtype = _strided(rgb, out, kinds, "float32, float16 or bfloat16")
     with torch.cuda.device(rgb.device):
         _check(load_library().harris_coarsity_typed(rgb.data_ptr(), dtype, B, H, W, ctypes.byref(lay), k, sobel_scale, window,
                                                     out.data_ptr(), kinds[out.dtype], _tuning_arg(tuning),
@@ -234,20 +227,7 @@ def harris_coarsity_quantized(rgb, out, q_scale: float, q_offset: float, k: floa
                               window: int = HARRIS_WINDOW_BOX, tuning=None, stream=None):
     """8-bit result: out (uint8 [batch][H-4][W-4], may be a view) = clamp(rint(fma(v, q_scale, q_offset)), 0, 255)."""
     import torch
-    if (not isinstance(rgb, torch.Tensor) or rgb.device.type != "cuda" or rgb.dtype not in (torch.float32, torch.uint8)
-            or rgb.dim() != 4 or rgb.shape[1] != 3):
-        raise TypeError("rgb must be a float32 or uint8 ROCm tensor of shape [batch][3][H][W]")
-    B, _, H, W = rgb.shape
-    if H < 4 or W < 4:
-        raise HarrisError(-2, harris_strerror(-2))
-    if (not isinstance(out, torch.Tensor) or out.device != rgb.device or out.dtype != torch.uint8
-            or tuple(out.shape) != (B, H - 4, W - 4)):
-        raise ValueError("out must be a uint8 tensor [batch][H-4][W-4] on rgb's device")
-    if (W > 1 and rgb.stride(3) != 1) or (W - 4 > 1 and out.stride(2) != 1):
-        raise ValueError("the last dimension of rgb and out must have stride 1")
-    lay = HarrisLayout(rgb.stride(2) if H > 1 else W, rgb.stride(1), rgb.stride(0) if B > 1 else 3 * rgb.stride(1),
-                       out.stride(1) if H - 4 > 1 else max(W - 4, 1), out.stride(0) if B > 1 else max(1, (H - 4) * out.stride(1)))
-    dtype = HARRIS_U8 if rgb.dtype == torch.uint8 else HARRIS_F32
+    B, H, W, lay, dtype = _strided(rgb, out, (torch.uint8,), "uint8")
     with torch.cuda.device(rgb.device):
         _check(load_library().harris_coarsity_quantized(rgb.data_ptr(), dtype, B, H, W, ctypes.byref(lay), k, sobel_scale, window,
                                                         q_scale, q_offset, out.data_ptr(), _tuning_arg(tuning),

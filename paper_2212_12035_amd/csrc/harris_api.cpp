@@ -4,12 +4,12 @@
 #include <math.h>
 #include <stdint.h>
 
-#include "harris.h"
+#include "harris_tuning.h"
 #include "harris_launch.h"
 
 namespace {
 
-constexpr int kVersion = 320;   // 0.3.2
+constexpr int kVersion = 400;   // 0.4.0
 
 bool power_of_two_aligned(uintptr_t p, unsigned bytes) { return (p & (uintptr_t)(bytes - 1)) == 0; }
 
@@ -33,11 +33,14 @@ bool px_fits(int px, int dtype, int out_dtype, int W, int rgb_align, int out_ali
 // word of such an access against the end of the row by itself, so the lane that straddles the
 // end of a row loads zeros beyond it and stores nothing there.  8-bit rows may start on any
 // byte: the kernel loads the aligned words that hold them and shifts.  Results: float32, or
-// 16-bit with rows on 4-byte boundaries (8-bit codes are stored as one word per lane and keep
-// the narrower lanes).
-bool px4_fits_word_aligned(int dtype, int out_dtype, int rgb_align, int out_align) {
+// 16-bit with rows that start on 4-byte boundaries and have an even number of columns: the
+// range check works on whole 32-bit words, so a word that held the last column of an odd row
+// together with two bytes behind it would either be dropped or written whole.  (8-bit codes
+// are stored as one word per lane and keep the narrower lanes.)
+bool px4_fits_word_aligned(int dtype, int out_dtype, int W, int rgb_align, int out_align) {
     if (dtype == HARRIS_F32 && rgb_align % 4 != 0) return false;
-    return out_dtype != HARRIS_OUT_U8 && out_align % 4 == 0;
+    if (out_dtype == HARRIS_OUT_U8 || out_align % 4 != 0) return false;
+    return out_dtype == HARRIS_OUT_F32 || W % 2 == 0;
 }
 
 int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int out_align, const harris_tuning* tuning,
@@ -47,6 +50,8 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
     if (W > (1 << 28)) return HARRIS_ERR_SHAPE;      // byte offsets within a row are 32-bit
     if (H > (1 << 30)) return HARRIS_ERR_SHAPE;      // row indices plus a tile's height stay within int
+    // Byte counts below are 64-bit: 16 bytes per pixel of at most 2^58 pixels would not fit.
+    if (batch > 0 && (long long)H * W > (1LL << 56) / batch) return HARRIS_ERR_SHAPE;
     if (rgb_align < 1 || out_align < out_elem_size(out_dtype)) return HARRIS_ERR_ARG;
     harris_tuning t = {0, 0, 0, 0, 0, 0u, 0};
     if (tuning) t = *tuning;
@@ -60,18 +65,18 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
 
     const int n = H - 4, m = W - 4;
     const bool tiles_allowed = (t.schedule == 0 || t.schedule == HARRIS_SCHEDULE_TILES) && t.prefetch == 0;
-    const bool word_aligned_px4 = tiles_allowed && px4_fits_word_aligned(dtype, out_dtype, rgb_align, out_align);
+    const bool word_aligned_px4 = tiles_allowed && px4_fits_word_aligned(dtype, out_dtype, W, rgb_align, out_align);
     if (t.px == 0) {
         t.px = 1;
         if (px_fits(4, dtype, out_dtype, W, rgb_align, out_align) || word_aligned_px4) t.px = 4;
         else if (px_fits(2, dtype, out_dtype, W, rgb_align, out_align)) t.px = 2;
-    } else if (!((t.px == 1 || t.px == 2 || t.px == 4 || t.px == 8) &&
+    } else if (!((t.px == 1 || t.px == 2 || t.px == 4) &&
                  (px_fits(t.px, dtype, out_dtype, W, rgb_align, out_align) || (t.px == 4 && word_aligned_px4)))) {
         return HARRIS_ERR_ARG;
     }
     if (t.rows < 0 || t.prefetch < 0 || t.waves_per_block < 0 || t.lds_kb < 0 || t.lds_kb > 64) return HARRIS_ERR_ARG;
-    // px = 8 and a prefetch depth exist only in the band schedule.
-    if (t.schedule == 0) t.schedule = t.px <= 4 && t.prefetch == 0 ? HARRIS_SCHEDULE_TILES : HARRIS_SCHEDULE_BANDS;
+    // A prefetch depth exists only in the band schedule.
+    if (t.schedule == 0) t.schedule = t.prefetch == 0 ? HARRIS_SCHEDULE_TILES : HARRIS_SCHEDULE_BANDS;
     if (out_dtype != HARRIS_OUT_F32 && t.schedule != HARRIS_SCHEDULE_TILES) return HARRIS_ERR_ARG;   // 16- and 8-bit results: tile kernel only
     // Strip borders on 64-byte boundaries of the result rows: the tile kernel with 16-byte lanes.
     // (A lane's stores must then be naturally aligned: borders can only lie between lanes.)
@@ -178,12 +183,11 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
         if (t.rows == 0 && t.waves_per_block == 0) { t.rows = tile_rw; t.waves_per_block = tile_nw; if (t.lds_kb == 0) t.lds_kb = tile_lds_kb; }
         if (t.rows == 0) t.rows = 4;
         if (t.waves_per_block == 0) t.waves_per_block = 4;
-        const bool rows_ok = t.rows == 4 || t.rows == 8 || (t.px == 4 && (t.rows == 5 || t.rows == 6 || t.rows == 9 || t.rows == 10));
+        const bool rows_ok = t.rows == 4 || (t.px == 4 && (t.rows == 5 || t.rows == 6 || t.rows == 8 || t.rows == 9 || t.rows == 10));
         if (!rows_ok || t.waves_per_block < 2 || t.waves_per_block > 16) return HARRIS_ERR_ARG;
         if (in_shifted && !(t.rows == 4 || t.rows == 8)) return HARRIS_ERR_ARG;
-        if (in_shifted && (t.flags & HARRIS_TUNE_FLAG_HANDOFF)) return HARRIS_ERR_ARG;
+        if (dtype == HARRIS_U8 && (t.flags & HARRIS_TUNE_FLAG_HANDOFF)) return HARRIS_ERR_ARG;   // ready flags: float32 input only
         if (t.prefetch != 0) return HARRIS_ERR_ARG;
-        if (t.px > 4) return HARRIS_ERR_ARG;                           // 8 rows of 8 pixels per lane do not fit the registers
         tile_rows = (long long)t.rows * t.waves_per_block - 4;
         // The reservation in force: at least the four gray rows each wavefront publishes.
         const int need_kb = (int)(((long long)t.waves_per_block * 4 * 64 * t.px * 4 + 1023) / 1024);
@@ -191,8 +195,8 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
     } else {
         if (t.lds_kb != 0) return HARRIS_ERR_ARG;                       // the band schedule uses no LDS
         const bool large = footprint > (256LL << 20);
-        if (t.prefetch == 0) t.prefetch = large ? 6 : 3;
-        if (!(t.prefetch == 2 || t.prefetch == 3 || t.prefetch == 6)) return HARRIS_ERR_ARG;
+        if (t.prefetch == 0) t.prefetch = 3;
+        if (t.prefetch != 3) return HARRIS_ERR_ARG;                     // the one depth the band kernels are built for
         if (t.waves_per_block == 0) t.waves_per_block = large ? 4 : 1;
         if (!(t.waves_per_block == 1 || t.waves_per_block == 2 || t.waves_per_block == 4)) return HARRIS_ERR_ARG;
         if (t.rows == 0) {

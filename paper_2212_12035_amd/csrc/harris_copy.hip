@@ -14,7 +14,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "harris.h"
 #include "harris_launch.h"
 
 namespace {

@@ -1,6 +1,7 @@
-// Unfused and partly fused Harris pipelines: the kernel groupings of the thesis's
-// section 3.5.3 (table "Four different kernel groupings"), as plain HIP kernels that
-// keep every intermediate image in device memory.
+// Unfused and partly fused Harris pipelines: the kernel groupings of the thesis's chapter 3,
+// section "Explicit Kernel Execution", subsection "Evaluating the Boilerplate Avoided through
+// Kernel Execution" (table "Four different kernel groupings"), as plain HIP kernels that keep
+// every intermediate image in device memory.
 //
 //   grouping 1: [gray] [Sx] [Sy] [x] [x] [x] [+] [+] [+] [coarsity]
 //   grouping 2: [gray] [Sx, Sy, x]  [+, coarsity]
@@ -16,7 +17,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "harris.h"
 #include "harris_launch.h"
 
 namespace {

@@ -1,4 +1,6 @@
-// Fused Harris coarsity kernel for gfx950 (MI355X) and its host-side launcher.
+// Device code of the fused Harris coarsity kernels for gfx950 (MI355X): included by the
+// translation units that instantiate them (harris_tiles_f32.hip, harris_tiles_u8.hip,
+// harris_bands.hip), never by host-only code.
 //
 // One kernel computes every stage of the Harris operator (thesis chapter 4,
 // section 4.2: grayscale, Sobel pair, products, 3x3 window sums, coarsity) and
@@ -32,13 +34,15 @@
 //    bands walk upwards, so two neighbouring bands begin on the rows they share.
 // In both, tiles are dealt to workgroups so that each XCD (own L2) gets one
 // contiguous run of tiles.
+#ifndef HARRIS_KERNELS_H
+#define HARRIS_KERNELS_H
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
 #include <type_traits>
 
-#include "harris.h"
+#include "harris_tuning.h"
 #include "harris_launch.h"
 
 namespace {
@@ -486,7 +490,8 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
     const unsigned lane = threadIdx.x % kWave;
     const unsigned wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     if constexpr (HANDOFF) {
-        // Every flag is cleared before any wavefront can look at one.  At this point the
+        // Every flag is cleared before any wavefront can look at one (the barrier orders the
+        // clearing stores before every later access of the workgroup).  At this point the
         // wavefronts of a workgroup are a few hundred cycles apart: the barrier costs nothing measurable.
         if (lane == 0) __hip_atomic_store(&ready[wave], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         __syncthreads();
@@ -611,10 +616,13 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
             for (int i = 0; i < PX; ++i) my_halo[(size_t)t * kWave * PX + i] = gc[i];
         }
         if constexpr (HANDOFF && t == 3) {
-            // The four rows are in LDS (LDS operations of a wavefront complete in order; the wait
-            // makes that explicit), then the flag.
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            if (lane == 0) __hip_atomic_store(&ready[wave], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            // Publish.  The lanes' writes of the four rows are ordered before lane 0's release
+            // store by a release fence, a barrier and an acquire fence at wavefront scope; the
+            // release store at workgroup scope then carries them to whoever acquires the flag.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (lane == 0) __hip_atomic_store(&ready[wave], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         if constexpr (t < 4) {
             row_step<(t < 2 ? 0 : 1), t % 3, PX, BINOM>(lb, gc, p.k, none);
@@ -631,11 +639,13 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
 
     if (wave + 1 < n_waves) {
         if constexpr (HANDOFF) {
-            // Wavefront wave + 1 sets its flag without depending on anybody (every wavefront runs
-            // through the code above unconditionally), so this wait ends.
-            while (__builtin_amdgcn_readfirstlane(__hip_atomic_load(&ready[wave + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) == 0u)
+            // Acquire load of the neighbour's flag: pairs with its release store, so the rows read
+            // below are the published ones.  The wait ends: all wavefronts of a workgroup are
+            // resident on the CU together (a workgroup is dispatched as a whole), and wavefront
+            // wave + 1 reaches its release store without waiting for anybody (every wavefront
+            // runs through the code above unconditionally; its loads always return).
+            while (__hip_atomic_load(&ready[wave + 1], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0u)
                 __builtin_amdgcn_s_sleep(4);
-            asm volatile("" ::: "memory");                      // the rows are read after the flag, not before
         }
         const float* below = halo_lds + ((size_t)(wave + 1) * 4 * kWave + lane) * PX;
         static_for<RW, RW + 4>([&](auto tt) {
@@ -673,122 +683,6 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
     }
 }
 
-template <typename In, int PX, int D>
-hipError_t launch_bands(const harris_launch::Params& p, dim3 grid, dim3 block, hipStream_t stream) {
-    const bool cached = p.flags & HARRIS_TUNE_CACHED_LOADS;
-    if (p.binomial) {
-        if (cached) hipLaunchKernelGGL((harris_fused_kernel<In, PX, D, kAuxDefault, true>), grid, block, 0, stream, p);
-        else hipLaunchKernelGGL((harris_fused_kernel<In, PX, D, kAuxNonTemporal, true>), grid, block, 0, stream, p);
-    } else {
-        if (cached) hipLaunchKernelGGL((harris_fused_kernel<In, PX, D, kAuxDefault, false>), grid, block, 0, stream, p);
-        else hipLaunchKernelGGL((harris_fused_kernel<In, PX, D, kAuxNonTemporal, false>), grid, block, 0, stream, p);
-    }
-    return hipGetLastError();
-}
-
-template <typename In, int PX, int RW>
-hipError_t launch_tiles(const harris_launch::Params& p, dim3 grid, dim3 block, hipStream_t stream) {
-    // The four gray rows each wavefront publishes; the planner may reserve more to bound the
-    // number of workgroups resident on a CU.
-    const size_t lds_needed = (size_t)(block.x / kWave) * 4 * kWave * PX * sizeof(float);
-    const size_t lds = p.lds_bytes > lds_needed ? p.lds_bytes : lds_needed;
-    const bool cached = p.flags & HARRIS_TUNE_CACHED_LOADS;
-    if (p.in_shifted) {
-        // 8-bit rows on any byte: kernels for 4 and 8 rows per wavefront, barrier hand-over.
-        if constexpr (std::is_same<In, uint8_t>::value && PX == 4 && (RW == 4 || RW == 8)) {
-            if (p.flags & HARRIS_TUNE_FLAG_HANDOFF) return hipErrorInvalidValue;
-            const bool keep = p.flags & HARRIS_TUNE_KEEP_SHARED_ROWS;
-            if (p.binomial) {
-                if (keep) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxKeepShared, true, false, true>), grid, block, lds, stream, p);
-                else if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, true, false, true>), grid, block, lds, stream, p);
-                else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, true, false, true>), grid, block, lds, stream, p);
-            } else {
-                if (keep) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxKeepShared, false, false, true>), grid, block, lds, stream, p);
-                else if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, false, false, true>), grid, block, lds, stream, p);
-                else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, false, false, true>), grid, block, lds, stream, p);
-            }
-            return hipGetLastError();
-        } else {
-            return hipErrorInvalidValue;
-        }
-    }
-    if constexpr (PX == 4) {
-        // Kernels that exist for 16-byte lanes only (the planner asks for them nowhere else).
-        if (p.flags & HARRIS_TUNE_FLAG_HANDOFF) {
-            if (p.binomial) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, true, true>), grid, block, lds, stream, p);
-            else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, false, true>), grid, block, lds, stream, p);
-            return hipGetLastError();
-        }
-        if (p.flags & HARRIS_TUNE_KEEP_SHARED_ROWS) {
-            if (p.binomial) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxKeepShared, true, false>), grid, block, lds, stream, p);
-            else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxKeepShared, false, false>), grid, block, lds, stream, p);
-            return hipGetLastError();
-        }
-    }
-    if (p.binomial) {
-        if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, true, false>), grid, block, lds, stream, p);
-        else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, true, false>), grid, block, lds, stream, p);
-    } else {
-        if (cached) hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxDefault, false, false>), grid, block, lds, stream, p);
-        else hipLaunchKernelGGL((harris_tile_kernel<In, PX, RW, kAuxNonTemporal, false, false>), grid, block, lds, stream, p);
-    }
-    return hipGetLastError();
-}
-
-template <typename In, int PX>
-hipError_t launch_px(const harris_launch::Params& p, const harris_tuning& t, dim3 grid, dim3 block, hipStream_t stream) {
-    if (t.schedule == HARRIS_SCHEDULE_TILES) {
-        if constexpr (PX <= 4) {
-            switch (t.rows) {
-                case 4: return launch_tiles<In, PX, 4>(p, grid, block, stream);
-                case 8: return launch_tiles<In, PX, 8>(p, grid, block, stream);
-                default: break;
-            }
-            if constexpr (PX == 4) {
-                switch (t.rows) {
-                    case 5: return launch_tiles<In, PX, 5>(p, grid, block, stream);
-                    case 6: return launch_tiles<In, PX, 6>(p, grid, block, stream);
-                    case 9: return launch_tiles<In, PX, 9>(p, grid, block, stream);
-                    case 10: return launch_tiles<In, PX, 10>(p, grid, block, stream);
-                    default: break;
-                }
-            }
-            return hipErrorInvalidValue;
-        } else {
-            return hipErrorInvalidValue;
-        }
-    }
-    if (p.out_kind != HARRIS_OUT_F32) return hipErrorInvalidValue;      // the band kernel stores float32 only
-    switch (t.prefetch) {
-        case 2: return launch_bands<In, PX, 2>(p, grid, block, stream);
-        case 3: return launch_bands<In, PX, 3>(p, grid, block, stream);
-        case 6: return launch_bands<In, PX, 6>(p, grid, block, stream);
-        default: return hipErrorInvalidValue;
-    }
-}
-
-template <typename In>
-hipError_t launch_in(const harris_launch::Params& p, const harris_tuning& t, dim3 grid, dim3 block, hipStream_t stream) {
-    switch (t.px) {
-        case 1: return launch_px<In, 1>(p, t, grid, block, stream);
-        case 2: return launch_px<In, 2>(p, t, grid, block, stream);
-        case 4: return launch_px<In, 4>(p, t, grid, block, stream);
-        case 8: return launch_px<In, 8>(p, t, grid, block, stream);
-        default: return hipErrorInvalidValue;
-    }
-}
-
 }  // namespace
 
-namespace harris_launch {
-
-int launch(const Params& p, const harris_tuning& shape, long long n_blocks, int dtype, void* stream) {
-    if (n_blocks != (long long)p.n_blocks || shape.waves_per_block != (int)p.waves_per_block) return HARRIS_ERR_LAUNCH;
-    const dim3 grid((unsigned)n_blocks), block((unsigned)(shape.waves_per_block * kWave));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = dtype == HARRIS_U8 ? launch_in<uint8_t>(p, shape, grid, block, s)
-                                      : launch_in<float>(p, shape, grid, block, s);
-    return e == hipSuccess ? HARRIS_OK : HARRIS_ERR_LAUNCH;
-}
-
-}  // namespace harris_launch
+#endif  // HARRIS_KERNELS_H

@@ -4,7 +4,7 @@
 
 #include <stddef.h>
 
-#include "harris.h"
+#include "harris_tuning.h"
 
 namespace harris_launch {
 
@@ -75,6 +75,13 @@ struct Params {
 // Enqueue the fused kernel.  `shape` must come from harris_plan (all fields set).
 // Returns a harris_status.
 int launch(const Params& p, const harris_tuning& shape, long long n_blocks, int dtype, void* stream);
+
+// The translation units that hold the kernels: each enqueues the instance that `shape` names
+// with `grid` workgroups of `block` threads and returns the hipError_t of the launch as int
+// (hipErrorInvalidValue for a shape it has no kernel for).
+int launch_tiles_f32(const Params& p, const harris_tuning& shape, unsigned grid, unsigned block, void* stream);
+int launch_tiles_u8(const Params& p, const harris_tuning& shape, unsigned grid, unsigned block, void* stream);
+int launch_bands(const Params& p, const harris_tuning& shape, int dtype, unsigned grid, unsigned block, void* stream);
 
 // Floats of workspace the grouped (unfused) pipelines need; 0 for an unknown grouping.
 size_t grouped_workspace_floats(int grouping, int batch, int H, int W);

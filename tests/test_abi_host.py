@@ -15,17 +15,22 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def pkg():
     import paper_2212_12035_amd as p
     if not os.path.exists(p.library_path()):
-        import __graft_entry__
-        __graft_entry__.build()
+        from paper_2212_12035_amd import build
+        build.build_library()
     p.load_library()
     return p
 
 
 def test_every_declared_symbol_is_exported(pkg):
-    header = open(os.path.join(ROOT, "include", "harris.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(harris_[a-z0-9_]+)\s*\(", header))
+    declared = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        header = open(os.path.join(ROOT, "include", name)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared |= set(re.findall(r"\b(harris_[a-z0-9_]+)\s*\(", header))
     assert declared == set(pkg.binding.EXPORTS)
+    # the operator's own header stands alone: no launch-shape knobs in it
+    public = open(os.path.join(ROOT, "include", "harris.h")).read()
+    assert "HARRIS_TUNE_" not in re.sub(r"/\*.*?\*/", "", public, flags=re.S) and "harris_plan" not in public
     lib = ctypes.CDLL(pkg.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -76,7 +81,7 @@ def test_plan_tile_arithmetic(pkg):
     t = dict(schedule=pkg.HARRIS_SCHEDULE_BANDS, px=4, rows=16, prefetch=3, waves_per_block=4, flags=pkg.HARRIS_TUNE_STREAM_LOADS | pkg.HARRIS_TUNE_PLAIN_STORES)
     shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=t)
     assert shape == dict(t, lds_kb=0) and blocks == 6 * 48          # 2 strips x 2 bands per workgroup: ceil(11/2) x ceil(96/2)
-    shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 3, 9, 9, tuning=dict(schedule=1, px=1, rows=2, prefetch=2, waves_per_block=1, flags=3))
+    shape, blocks = pkg.harris_plan(pkg.HARRIS_F32, 3, 9, 9, tuning=dict(schedule=1, px=1, rows=2, prefetch=3, waves_per_block=1, flags=3))
     assert blocks == 3 * 3 * 1
     # tiles: 8 wavefronts x 8 rows give 60 result rows per tile -> 26 tiles down, 11 across,
     # one workgroup each
@@ -166,7 +171,7 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     bands, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=dict(schedule=1))
     assert (bands["rows"], bands["prefetch"], bands["waves_per_block"]) == (17, 3, 1) and blocks == 1001
     bands, blocks = pkg.harris_plan(pkg.HARRIS_F32, 64, 1080, 1920, tuning=dict(schedule=1))
-    assert (bands["rows"], bands["prefetch"], bands["waves_per_block"]) == (32, 6, 4) and blocks == 64 * 17 * 4
+    assert (bands["rows"], bands["prefetch"], bands["waves_per_block"]) == (32, 3, 4) and blocks == 64 * 17 * 4
 
 
 def test_plan_rejects_bad_arguments(pkg):
@@ -177,6 +182,8 @@ def test_plan_rejects_bad_arguments(pkg):
         ((0, 2 ** 31 - 1, 4096, 4096), -2),         # more tiles than a grid can hold
         ((0, 1, 8, 2 ** 28 + 4), -2),               # row offsets would not fit 32 bits
         ((0, 1, 2 ** 30 + 1, 8), -2),               # row indices would not fit int
+        ((0, 2 ** 31 - 1, 2 ** 30, 2 ** 28), -2),   # byte counts would not fit 64 bits
+        ((1, 2 ** 20, 2 ** 30, 2 ** 28), -2),
     ]:
         with pytest.raises(E) as e:
             pkg.harris_plan(*args)
@@ -184,12 +191,16 @@ def test_plan_rejects_bad_arguments(pkg):
     for bad in (dict(px=3), dict(px=4, prefetch=5), dict(schedule=1, px=4, waves_per_block=3), dict(waves_per_block=1), dict(flags=256), dict(flags=12), dict(flags=48), dict(flags=64), dict(flags=64 | 4), dict(schedule=1, flags=64 | 8), dict(px=2, flags=64 | 8),
                 dict(flags=128 | 4), dict(flags=128 | 64 | 8), dict(schedule=1, flags=128), dict(px=2, flags=128), dict(schedule=1, flags=16), dict(px=2, flags=16), dict(rows=-1),
                 dict(schedule=3), dict(schedule=2, rows=7), dict(schedule=2, px=2, rows=5), dict(schedule=2, waves_per_block=1), dict(schedule=2, waves_per_block=17),
-                dict(schedule=2, prefetch=3), dict(schedule=2, px=8), dict(lds_kb=65), dict(lds_kb=-1), dict(schedule=1, lds_kb=16)):
+                dict(schedule=2, prefetch=3), dict(schedule=2, px=8), dict(px=8), dict(prefetch=2), dict(schedule=1, prefetch=6), dict(schedule=2, px=2, rows=8),
+                dict(lds_kb=65), dict(lds_kb=-1), dict(schedule=1, lds_kb=16)):
         with pytest.raises(E) as e:
             pkg.harris_plan(0, 1, 64, 64, tuning=bad)
         assert e.value.status == -3
     with pytest.raises(E):                          # px = 4 in the band schedule needs W % 4 == 0
         pkg.harris_plan(0, 1, 64, 98, tuning=dict(schedule=1, px=4))
+    with pytest.raises(E) as e:                     # ready flags: float32 input only
+        pkg.harris_plan(pkg.HARRIS_U8, 1, 64, 64, tuning=dict(flags=pkg.HARRIS_TUNE_FLAG_HANDOFF))
+    assert e.value.status == -3
 
 
 def test_plan_for_16_bit_results(pkg):
@@ -206,6 +217,13 @@ def test_plan_for_16_bit_results(pkg):
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, F16, 1, 1536, 2560, tuning=dict(flags=pkg.HARRIS_TUNE_ALIGNED_STORES))[1] % 12 == 0
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, BF16, 1, 64, 96, out_align=4)[0]["px"] == 4      # word-aligned 8-byte stores
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, BF16, 1, 64, 96, out_align=2)[0]["px"] == 1
+    # rows with an odd number of 16-bit results: the last column would share a 32-bit word with what lies behind the row
+    for odd in (97, 131, 1001):
+        assert pkg.harris_plan_typed(pkg.HARRIS_F32, F16, 2, 64, odd, out_align=4)[0]["px"] == 1
+        assert pkg.harris_plan_typed(pkg.HARRIS_U8, BF16, 2, 64, odd, rgb_align=1, out_align=4)[0]["px"] == 1
+        assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_F32, 2, 64, odd, out_align=4)[0]["px"] == 4
+        with pytest.raises(pkg.HarrisError):
+            pkg.harris_plan_typed(pkg.HARRIS_F32, F16, 2, 64, odd, out_align=4, tuning=dict(px=4))
     assert pkg.harris_plan_typed(pkg.HARRIS_F32, pkg.HARRIS_OUT_F32, 1, 1536, 2560) == pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)
     for bad in (dict(out_dtype=4), dict(out_dtype=F16, tuning=dict(schedule=1)), dict(out_dtype=F16, tuning=dict(prefetch=3)),
                 dict(out_dtype=F16, out_align=1), dict(out_dtype=F16, tuning=dict(px=8))):
@@ -322,7 +340,10 @@ def test_product_sources_never_reach_for_the_oracle():
             if name.endswith((".py", ".hip", ".cpp", ".h")):
                 text = open(os.path.join(base, name)).read()
                 assert "oracle" not in text.lower(), os.path.join(base, name)
-    assert "oracle" not in open(os.path.join(ROOT, "include", "harris.h")).read().lower()
+    for name in os.listdir(os.path.join(ROOT, "include")):
+        assert "oracle" not in open(os.path.join(ROOT, "include", name)).read().lower()
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    assert "__graft_entry__" not in bench              # the benchmark builds the library by the package's own build step
     assert "paper_2212_12035_amd" not in open(os.path.join(ROOT, "oracle", "harris_oracle.py")).read()
     assert "harris.h" not in open(os.path.join(ROOT, "oracle", "harris_ref.cpp")).read()
 
