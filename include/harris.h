@@ -47,7 +47,9 @@ typedef enum harris_status {
                                 pitches smaller than the image                               */
     HARRIS_ERR_ARG = -3,     /* k or sobel_scale not finite, unknown dtype/window/tuning,
                                 misaligned pointer                                          */
-    HARRIS_ERR_LAUNCH = -4   /* the HIP runtime refused the kernel launch                   */
+    HARRIS_ERR_LAUNCH = -4,  /* the HIP runtime refused the kernel launch                   */
+    HARRIS_ERR_SCRATCH = -5  /* harris_coarsity_grouped_static: the problem needs more than
+                                HARRIS_GROUPED_SCRATCH_BYTES of intermediates               */
 } harris_status;
 
 /* Element type of the input image. */
@@ -191,6 +193,30 @@ int harris_coarsity_grouped(const void* rgb, int dtype, int batch, int H, int W,
 
 /* Workspace bytes harris_coarsity_grouped needs; 0 for grouping 4; -1 for invalid arguments. Host only. */
 long long harris_grouped_workspace_bytes(int grouping, int batch, int H, int W);
+
+/*
+ * harris_coarsity_grouped (groupings 1-3) for callers that cannot allocate and have no
+ * workspace to bring: code under HIP stream capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The intermediate images live in a fixed array of HARRIS_GROUPED_SCRATCH_BYTES that
+ * is part of the library's device code (each GPU the library runs on holds it until the process
+ * ends); this call allocates and frees nothing, on the host or on the device.
+ *   - The problem must fit: harris_grouped_workspace_bytes(grouping, batch, H, W) <=
+ *     HARRIS_GROUPED_SCRATCH_BYTES (64 MiB: grouping 3 up to about 5.5 million pixels per call,
+ *     grouping 2 up to 4.1 million, e.g. one 1536 x 2560 image, grouping 1 up to 1.8 million),
+ *     else HARRIS_ERR_SCRATCH and nothing is enqueued.  Grouping 4 needs no intermediates and
+ *     takes any size.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap in time (different
+ *     streams, or one stream and a replaying graph) race on it and must be serialised by the
+ *     caller.  Nothing in it needs clearing: every kernel writes the intermediates it produces
+ *     completely before a later kernel reads them, whatever an earlier call left there.
+ *   - The device whose stream is given must be the current device of the calling thread.  The
+ *     first call on a device looks up the array's address there (and, like any first launch,
+ *     lets the runtime load the library's device code): make it outside stream capture.
+ * Other arguments, results and errors as harris_coarsity_grouped.
+ */
+#define HARRIS_GROUPED_SCRATCH_BYTES (64u << 20)
+int harris_coarsity_grouped_static(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale,
+                                   int window, int grouping, float* out, void* stream);
 
 /* Static, NUL-terminated description of a harris_status value. */
 const char* harris_strerror(int status);

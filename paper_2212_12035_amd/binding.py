@@ -22,7 +22,7 @@ _LIB_PATH = os.path.join(_HERE, "libharris.so")
 #: every symbol include/harris.h and include/harris_tuning.h declare
 EXPORTS = ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan", "harris_plan_typed",
            "harris_coarsity_pitched", "harris_coarsity_typed", "harris_coarsity_quantized", "harris_coarsity_grouped",
-           "harris_grouped_workspace_bytes", "harris_probe_copy", "harris_strerror", "harris_version")
+           "harris_grouped_workspace_bytes", "harris_coarsity_grouped_static", "harris_probe_copy", "harris_strerror", "harris_version")
 HARRIS_OUT_F32, HARRIS_OUT_F16, HARRIS_OUT_BF16, HARRIS_OUT_U8 = 0, 1, 2, 3
 
 
@@ -83,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     lib.harris_plan_typed.argtypes = [ci, ci, ci, ci, ci, ci, ci, tp, tp, ctypes.POINTER(ctypes.c_longlong)]
     lib.harris_plan_typed.restype = ci
     lib.harris_coarsity_grouped.argtypes = [vp, ci, ci, ci, ci, cf, cf, ci, ci, vp, ctypes.c_longlong, vp, vp]
+    lib.harris_coarsity_grouped_static.argtypes = [vp, ci, ci, ci, ci, cf, cf, ci, ci, vp, vp]
+    lib.harris_coarsity_grouped_static.restype = ci
     lib.harris_grouped_workspace_bytes.argtypes = [ci, ci, ci, ci]
     lib.harris_grouped_workspace_bytes.restype = ctypes.c_longlong
     lib.harris_probe_copy.argtypes = [vp, ci, ci, ci, ci, vp, vp]
@@ -268,6 +270,26 @@ def harris_coarsity_grouped(rgb, k: float = 0.04, sobel_scale: float = 1.0, wind
         _check(load_library().harris_coarsity_grouped(rgb.data_ptr(), dtype, B, H, W, k, sobel_scale, window, grouping,
                                                       workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                                       out.data_ptr(), _stream_ptr(stream, rgb.device)))
+    return out
+
+
+HARRIS_GROUPED_SCRATCH_BYTES = 64 << 20
+
+
+def harris_coarsity_grouped_static(rgb, out, k: float = 0.04, sobel_scale: float = 1.0, window: int = HARRIS_WINDOW_BOX,
+                                   grouping: int = 1, stream=None):
+    """harris_coarsity_grouped on the library's own fixed scratch array: nothing is allocated, here or
+    in the library, so `out` (float32 [batch][H-4][W-4], contiguous) must be given."""
+    import torch
+    if not isinstance(rgb, torch.Tensor) or rgb.dtype not in (torch.float32, torch.uint8):
+        raise TypeError("rgb must be a float32 or uint8 torch tensor")
+    if out is None:
+        raise ValueError("out must be given: this entry point allocates nothing")
+    B, H, W, out = _prepare(rgb, out, rgb.dtype)
+    dtype = HARRIS_U8 if rgb.dtype == torch.uint8 else HARRIS_F32
+    with torch.cuda.device(rgb.device):
+        _check(load_library().harris_coarsity_grouped_static(rgb.data_ptr(), dtype, B, H, W, k, sobel_scale, window, grouping,
+                                                             out.data_ptr(), _stream_ptr(stream, rgb.device)))
     return out
 
 

@@ -426,6 +426,24 @@ int harris_coarsity_grouped(const void* rgb, int dtype, int batch, int H, int W,
                                          grouping, static_cast<float*>(workspace), out, stream);
 }
 
+int harris_coarsity_grouped_static(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale,
+                                   int window, int grouping, float* out, void* stream) {
+    if (grouping < 1 || grouping > 4) return HARRIS_ERR_ARG;
+    if (grouping == 4) return harris_coarsity_ex(rgb, dtype, batch, H, W, k, sobel_scale, window, out, nullptr, stream);
+    if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
+    if (batch == 0 || H == 4 || W == 4)      // empty result: the remaining argument checks, no work, no scratch
+        return harris_coarsity_grouped(rgb, dtype, batch, H, W, k, sobel_scale, window, grouping, nullptr, 0, out, stream);
+    // The gray image alone is 4 bytes per pixel; checked in doubles first, since the exact count
+    // below is 64-bit arithmetic and absurd shapes would not fit it.
+    if (4.0 * (double)batch * (double)H * (double)W > (double)HARRIS_GROUPED_SCRATCH_BYTES) return HARRIS_ERR_SCRATCH;
+    const long long need = harris_grouped_workspace_bytes(grouping, batch, H, W);
+    if (need < 0 || need > (long long)HARRIS_GROUPED_SCRATCH_BYTES) return HARRIS_ERR_SCRATCH;
+    if (rgb == nullptr || out == nullptr) return HARRIS_ERR_NULL;
+    float* ws = harris_launch::scratch_of_current_device();
+    if (ws == nullptr) return HARRIS_ERR_LAUNCH;
+    return harris_coarsity_grouped(rgb, dtype, batch, H, W, k, sobel_scale, window, grouping, ws, need, out, stream);
+}
+
 int harris_probe_copy(const void* rgb, int dtype, int batch, int H, int W, float* out, void* stream) {
     if (dtype != HARRIS_F32 && dtype != HARRIS_U8) return HARRIS_ERR_ARG;
     if (batch < 0 || H < 4 || W < 4) return HARRIS_ERR_SHAPE;
@@ -444,6 +462,7 @@ const char* harris_strerror(int status) {
         case HARRIS_ERR_SHAPE: return "invalid shape: batch < 0, H < 4, W < 4, too many tiles, or pitches smaller than the image";
         case HARRIS_ERR_ARG: return "invalid argument: non-finite k or sobel_scale, misaligned pointer, unknown dtype, window, grouping or tuning, workspace too small";
         case HARRIS_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+        case HARRIS_ERR_SCRATCH: return "the problem needs more scratch memory than the library's fixed buffer holds (HARRIS_GROUPED_SCRATCH_BYTES)";
         default: return "unknown harris_status";
     }
 }

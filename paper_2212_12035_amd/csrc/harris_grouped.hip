@@ -16,8 +16,16 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <mutex>
 
 #include "harris_launch.h"
+
+// Intermediate images for harris_coarsity_grouped_static: callers that cannot allocate (code
+// under stream capture, serving loops) get the groupings' workspace from here.  Each GPU the
+// library runs on holds its own copy of the array, at its own address, until the process ends.
+// Host code never uses this name as an address: it asks for the device's address once per
+// device (scratch_of_current_device) and hands that pointer to the kernels.
+static __device__ __align__(256) float scratch[HARRIS_GROUPED_SCRATCH_BYTES / sizeof(float)];
 
 namespace {
 
@@ -196,6 +204,23 @@ int launch_grouped(const void* rgb, int dtype, int batch, int H, int W, float k,
         hipLaunchKernelGGL(products_window_coarsity_kernel, grid2d(w4, h4, batch), blk2, 0, st, ix, iy, out, h4, w4, k, binomial);
     }
     return hipGetLastError() == hipSuccess ? HARRIS_OK : HARRIS_ERR_LAUNCH;
+}
+
+// Device address of `scratch` on the current device, looked up once per device (with that
+// device current, as now) and kept.  NULL if the runtime cannot say.
+float* scratch_of_current_device() {
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static float* known[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> hold(lock);
+    if (known[dev] == nullptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        known[dev] = static_cast<float*>(ptr);
+    }
+    return known[dev];
 }
 
 }  // namespace harris_launch

@@ -90,6 +90,10 @@ size_t grouped_workspace_floats(int grouping, int batch, int H, int W);
 int launch_grouped(const void* rgb, int dtype, int batch, int H, int W, float k, float sobel_scale, int binomial,
                    int grouping, float* workspace, float* out, void* stream);
 
+// Device address, on the current device, of the library's fixed scratch array of
+// HARRIS_GROUPED_SCRATCH_BYTES bytes (see harris_coarsity_grouped_static); NULL on failure.
+float* scratch_of_current_device();
+
 // Enqueue the streaming-copy probe (see harris_probe_copy).  Returns a harris_status.
 int launch_copy_probe(const void* rgb, int dtype, int batch, int H, int W, float* out, void* stream);
 

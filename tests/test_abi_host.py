@@ -39,8 +39,8 @@ def test_every_declared_symbol_is_exported(pkg):
 def test_version_and_strerror(pkg):
     assert pkg.harris_version() >= 100
     assert pkg.harris_strerror(0) == "success"
-    msgs = {pkg.harris_strerror(s) for s in (-1, -2, -3, -4)}
-    assert len(msgs) == 4 and all(m and m != "unknown harris_status" for m in msgs)
+    msgs = {pkg.harris_strerror(s) for s in (-1, -2, -3, -4, -5)}
+    assert len(msgs) == 5 and all(m and m != "unknown harris_status" for m in msgs)
     assert pkg.harris_strerror(-99) == "unknown harris_status"
 
 
@@ -308,6 +308,25 @@ def test_grouped_workspace_sizes_and_validation(pkg):
     assert lib.harris_coarsity_grouped(one, 0, 1, H, W, 0.04, 1.0, 0, 1, None, need, one, None) == -1
     assert lib.harris_coarsity_grouped(one, 0, 1, 3, W, 0.04, 1.0, 0, 2, one, need, one, None) == -2
     assert lib.harris_coarsity_grouped(None, 0, 0, H, W, 0.04, 1.0, 0, 3, None, 0, None, None) == 0
+
+
+def test_static_scratch_entry_rejects_what_does_not_fit(pkg):
+    # Checked on the host before anything touches a device.
+    lib = pkg.load_library()
+    one = ctypes.c_void_p(4096)
+    cap = pkg.HARRIS_GROUPED_SCRATCH_BYTES
+    assert cap == 64 << 20
+    assert pkg.harris_grouped_workspace_bytes(2, 1, 1536, 2560) <= cap < pkg.harris_grouped_workspace_bytes(1, 1, 1536, 2560)
+    assert lib.harris_coarsity_grouped_static(one, 0, 1, 1536, 2560, 0.04, 1.0, 0, 1, one, None) == -5
+    assert lib.harris_coarsity_grouped_static(one, 0, 64, 1080, 1920, 0.04, 1.0, 0, 3, one, None) == -5
+    assert lib.harris_coarsity_grouped_static(one, 0, 2 ** 31 - 1, 2 ** 30, 2 ** 28, 0.04, 1.0, 0, 2, one, None) == -5
+    assert lib.harris_coarsity_grouped_static(one, 0, 1, 64, 64, 0.04, 1.0, 0, 0, one, None) == -3      # grouping 0
+    assert lib.harris_coarsity_grouped_static(one, 0, 1, 64, 64, 0.04, 1.0, 0, 5, one, None) == -3
+    assert lib.harris_coarsity_grouped_static(one, 0, 1, 3, 64, 0.04, 1.0, 0, 1, one, None) == -2
+    assert lib.harris_coarsity_grouped_static(None, 0, 1, 64, 64, 0.04, 1.0, 0, 1, one, None) == -1
+    assert lib.harris_coarsity_grouped_static(None, 0, 0, 64, 64, 0.04, 1.0, 0, 2, None, None) == 0       # empty: no work, no scratch
+    assert lib.harris_coarsity_grouped_static(None, 0, 3, 4, 64, 0.04, 1.0, 0, 3, None, None) == 0
+    assert "scratch" in pkg.harris_strerror(-5)
 
 
 def test_pitched_entry_validates_the_layout(pkg):
