@@ -76,6 +76,7 @@ def parse():
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-groupings", action="store_true", help="skip timing the unfused kernel groupings")
+    ap.add_argument("--probes", action="store_true", help="also time pure read and pure write streams of the launch's bytes")
     ap.add_argument("--warm-cache", action="store_true", help="reuse one buffer pair (cache-resident; not the roofline number)")
     ap.add_argument("--out-dtype", choices=("f32", "f16", "bf16", "u8"), default="f32",
                     help="type the result is stored in (the arithmetic stays float32; u8: codes rint(v + 128) clamped); "
@@ -239,7 +240,7 @@ def main():
             rc = lib.harris_probe_copy(a, dtype_code, B, H, W, o, sptr)
             if rc != 0:
                 raise RuntimeError(pkg.harris_strerror(rc))
-        for i in range(max(3, reps // 4)):
+        for i in range(max(12, reps // 4)):     # untimed, and no synchronisation before the pair: a busy queue, as for the Harris figure
             pstep(i)
         p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         p0.record(stream)
@@ -252,6 +253,34 @@ def main():
                  "what": "harris_probe_copy: reads 3 planes, writes 1 float per result pixel, nothing else"}
         step(0)                                   # pair 0 holds the fused kernel's result again
         torch.cuda.synchronize(dev)
+
+    # Pure streams of the launch's algorithmic bytes, reads alone and writes alone, on rotating
+    # buffers of their own: with the copy probe they bound what this many bytes, cold, can reach.
+    streams = None
+    if args.probes:
+        sbytes = algo_bytes - algo_bytes % 16
+        bufs = [torch.randint(0, 256, (sbytes,), dtype=torch.uint8, device=dev) for _ in range(n_pairs)]
+        sink = torch.zeros(64, dtype=torch.uint8, device=dev)
+        streams = {"bytes": sbytes}
+        reps = max(20, min(400, args.steps // 4))
+        for kind, name in ((pkg.HARRIS_PROBE_READ, "read"), (pkg.HARRIS_PROBE_WRITE, "write")):
+            def sstep(i, kind=kind):
+                b = bufs[i % n_pairs]
+                rc = lib.harris_probe_stream(kind, ctypes.c_void_p(b.data_ptr()), ctypes.c_void_p(sink.data_ptr() if kind == pkg.HARRIS_PROBE_READ else b.data_ptr()), sbytes, sptr)
+                if rc != 0:
+                    raise RuntimeError(pkg.harris_strerror(rc))
+            for i in range(max(12, reps // 4)):
+                sstep(i)
+            q0, q1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            q0.record(stream)
+            for i in range(reps):
+                sstep(i)
+            q1.record(stream)
+            torch.cuda.synchronize(dev)
+            us = q0.elapsed_time(q1) * 1e3 / reps
+            streams[name + "_us"] = round(us, 3)
+            streams[name + "_GB/s"] = round(sbytes / (us * 1e-6) / 1e9, 1)
+        del bufs
 
     # Correctness of what was timed: pair 0 against the oracle (also the CPU baseline).
     got = outs[0].float().cpu().numpy()
@@ -321,6 +350,7 @@ def main():
                      "launch_us_single_median": round(single_med_us, 3),
                      "frac_of_copy_probe": round(achieved / probe["GB/s"], 4) if probe else None},
         "copy_probe": probe,
+        "stream_probes": streams,
         "cpu_baseline": cpu,
         "kernel_groupings": groupings,
         "max_abs_err_vs_oracle": max_err, "err_bound": bound, "rounding": rounding,

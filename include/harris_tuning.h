@@ -111,6 +111,21 @@ int harris_plan_typed(int dtype, int out_dtype, int batch, int H, int W, int rgb
  */
 int harris_probe_copy(const void* rgb, int dtype, int batch, int H, int W, float* out, void* stream);
 
+/*
+ * Measurement aid: a pure stream of `bytes` bytes, for the ceilings of reads alone and of writes
+ * alone beside harris_probe_copy's mix.
+ *   kind HARRIS_PROBE_READ   every byte of src[0 .. bytes) is loaded once (16 bytes per lane,
+ *                            non-temporal) and nothing is stored; dst must point to at least 4
+ *                            writable bytes (a sink that keeps the loads alive and stays untouched).
+ *   kind HARRIS_PROBE_WRITE  every byte of dst[0 .. bytes) is written once with a pattern of no
+ *                            meaning; src is ignored.
+ * src and dst are device pointers, 16-byte aligned, bytes a multiple of 16 (else HARRIS_ERR_ARG);
+ * bytes == 0 succeeds without work.
+ */
+#define HARRIS_PROBE_READ 1
+#define HARRIS_PROBE_WRITE 2
+int harris_probe_stream(int kind, const void* src, void* dst, long long bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ _LIB_PATH = os.path.join(_HERE, "libharris.so")
 #: every symbol include/harris.h and include/harris_tuning.h declare
 EXPORTS = ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan", "harris_plan_typed",
            "harris_coarsity_pitched", "harris_coarsity_typed", "harris_coarsity_quantized", "harris_coarsity_grouped",
-           "harris_grouped_workspace_bytes", "harris_coarsity_grouped_static", "harris_probe_copy", "harris_strerror", "harris_version")
+           "harris_grouped_workspace_bytes", "harris_coarsity_grouped_static", "harris_probe_copy", "harris_probe_stream", "harris_strerror", "harris_version")
 HARRIS_OUT_F32, HARRIS_OUT_F16, HARRIS_OUT_BF16, HARRIS_OUT_U8 = 0, 1, 2, 3
 
 
@@ -89,6 +89,8 @@ def load_library() -> ctypes.CDLL:
     lib.harris_grouped_workspace_bytes.restype = ctypes.c_longlong
     lib.harris_probe_copy.argtypes = [vp, ci, ci, ci, ci, vp, vp]
     lib.harris_probe_copy.restype = ci
+    lib.harris_probe_stream.argtypes = [ci, vp, vp, ctypes.c_longlong, vp]
+    lib.harris_probe_stream.restype = ci
     for name in ("harris_coarsity", "harris_coarsity_u8", "harris_coarsity_ex", "harris_plan", "harris_version",
                  "harris_coarsity_grouped"):
         getattr(lib, name).restype = ci
@@ -247,6 +249,17 @@ def harris_probe_copy(rgb, out=None, stream=None):
     with torch.cuda.device(rgb.device):
         _check(load_library().harris_probe_copy(rgb.data_ptr(), dtype, B, H, W, out.data_ptr(), _stream_ptr(stream, rgb.device)))
     return out
+
+
+HARRIS_PROBE_READ, HARRIS_PROBE_WRITE = 1, 2
+
+
+def harris_probe_stream(kind: int, src, dst, nbytes: int, stream=None):
+    """A pure read (kind 1: src -> nowhere) or write (kind 2: pattern -> dst) stream of nbytes bytes."""
+    import torch
+    with torch.cuda.device(dst.device):
+        _check(load_library().harris_probe_stream(kind, src.data_ptr() if src is not None else None, dst.data_ptr(), nbytes,
+                                                  _stream_ptr(stream, dst.device)))
 
 
 def harris_grouped_workspace_bytes(grouping: int, batch: int, H: int, W: int) -> int:

@@ -18,7 +18,13 @@
 
 namespace {
 
-constexpr int kNonTemporal = 2;
+#ifndef HARRIS_PROBE_LOAD_AUX
+#define HARRIS_PROBE_LOAD_AUX 2
+#endif
+#ifndef HARRIS_PROBE_STORE_AUX
+#define HARRIS_PROBE_STORE_AUX 2
+#endif
+constexpr int kNonTemporal = HARRIS_PROBE_LOAD_AUX, kStoreNonTemporal = HARRIS_PROBE_STORE_AUX;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, uint32_t bytes) {
@@ -54,7 +60,7 @@ __global__ __launch_bounds__(256) void copy_probe_f32(const float* rgb, float* o
         w.y = __float_as_uint(__uint_as_float(v[r][0].y) + __uint_as_float(v[r][1].y) + __uint_as_float(v[r][2].y));
         w.z = __float_as_uint(__uint_as_float(v[r][0].z) + __uint_as_float(v[r][1].z) + __uint_as_float(v[r][2].z));
         w.w = __float_as_uint(__uint_as_float(v[r][0].w) + __uint_as_float(v[r][1].w) + __uint_as_float(v[r][2].w));
-        __builtin_amdgcn_raw_buffer_store_b128(w, rsrc(dst + chunk[r] * 256, live[r] * 4u), lane * 16u, 0, kNonTemporal);
+        __builtin_amdgcn_raw_buffer_store_b128(w, rsrc(dst + chunk[r] * 256, live[r] * 4u), lane * 16u, 0, kStoreNonTemporal);
     }
 }
 
@@ -92,13 +98,66 @@ __global__ __launch_bounds__(256) void copy_probe_u8(const uint8_t* rgb, float* 
         w.y = __float_as_uint((float)(((a >> 8) & 0xffu) + ((b >> 8) & 0xffu) + ((c >> 8) & 0xffu)));
         w.z = __float_as_uint((float)(((a >> 16) & 0xffu) + ((b >> 16) & 0xffu) + ((c >> 16) & 0xffu)));
         w.w = __float_as_uint((float)((a >> 24) + (b >> 24) + (c >> 24)));
-        __builtin_amdgcn_raw_buffer_store_b128(w, drs, 1024u * q + lane * 16u, 0, kNonTemporal);
+        __builtin_amdgcn_raw_buffer_store_b128(w, drs, 1024u * q + lane * 16u, 0, kStoreNonTemporal);
+    }
+}
+
+// Pure streams, for the ceiling of reads alone and of writes alone: a wavefront moves kRun chunks
+// of 1 KB (16 bytes per lane), non-temporal, through buffer descriptors like everything else here.
+// The reading kernel folds what it loads into one word per lane and stores it only if that word
+// equals a constant the host passes (one lane in four billion for random data, none for the
+// zeros the benchmark reads): this keeps the loads alive and writes nothing.
+template <int kRun>
+__global__ __launch_bounds__(256) void read_probe(const uint32_t* src, uint32_t* sink, unsigned long long chunks, unsigned long long bytes, uint32_t never) {
+    const unsigned lane = threadIdx.x % 64;
+    const unsigned long long wave = (unsigned long long)blockIdx.x * 4 + threadIdx.x / 64;
+    u32x4 v[kRun];
+#pragma unroll
+    for (int r = 0; r < kRun; ++r) {
+        unsigned long long chunk = wave * kRun + r;
+        const bool inside = chunk < chunks;
+        if (!inside) chunk = 0;
+        const unsigned long long left = bytes - chunk * 1024;
+        const uint32_t live = inside ? (uint32_t)(left < 1024 ? left : 1024) : 0u;
+        v[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrc(src + chunk * 256, live), lane * 16u, 0, kNonTemporal);
+    }
+    uint32_t fold = 0;
+#pragma unroll
+    for (int r = 0; r < kRun; ++r) fold ^= v[r].x ^ (v[r].y << 1) ^ (v[r].z << 2) ^ (v[r].w << 3);
+    if (fold == never) sink[0] = fold;
+}
+
+template <int kRun>
+__global__ __launch_bounds__(256) void write_probe(uint32_t* dst, unsigned long long chunks, unsigned long long bytes) {
+    const unsigned lane = threadIdx.x % 64;
+    const unsigned long long wave = (unsigned long long)blockIdx.x * 4 + threadIdx.x / 64;
+    const u32x4 w = {lane, (uint32_t)wave, 0u, 0x3f800000u};
+#pragma unroll
+    for (int r = 0; r < kRun; ++r) {
+        unsigned long long chunk = wave * kRun + r;
+        const bool inside = chunk < chunks;
+        if (!inside) chunk = 0;
+        const unsigned long long left = bytes - chunk * 1024;
+        const uint32_t live = inside ? (uint32_t)(left < 1024 ? left : 1024) : 0u;
+        __builtin_amdgcn_raw_buffer_store_b128(w, rsrc(dst + chunk * 256, live), lane * 16u, 0, kStoreNonTemporal);
     }
 }
 
 }  // namespace
 
 namespace harris_launch {
+
+int launch_stream_probe(int kind, const void* src, void* dst, long long bytes, void* stream) {
+    constexpr unsigned long long kRun = 4;
+    const unsigned long long chunks = ((unsigned long long)bytes + 1023) / 1024, waves = (chunks + kRun - 1) / kRun, blocks = (waves + 3) / 4;
+    if (blocks > 0x7fffffffULL) return HARRIS_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (kind == HARRIS_PROBE_READ)
+        hipLaunchKernelGGL((read_probe<kRun>), dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const uint32_t*>(src), static_cast<uint32_t*>(dst), chunks, (unsigned long long)bytes, 0x9e3779b9u);
+    else
+        hipLaunchKernelGGL((write_probe<kRun>), dim3((unsigned)blocks), dim3(256), 0, s, static_cast<uint32_t*>(dst), chunks, (unsigned long long)bytes);
+    return hipGetLastError() == hipSuccess ? HARRIS_OK : HARRIS_ERR_LAUNCH;
+}
 
 int launch_copy_probe(const void* rgb, int dtype, int batch, int H, int W, float* out, void* stream) {
     const unsigned long long count = (unsigned long long)(H - 4) * (W - 4), plane = (unsigned long long)H * W;

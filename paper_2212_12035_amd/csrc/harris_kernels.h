@@ -82,22 +82,38 @@ __device__ __forceinline__ void fetch_halo(float (&a)[PX + 2]) {
 
 // ---------------------------------------------------------------- row loads and stores
 
-// Cache policy of the accesses (the "aux" operand of the buffer instructions):
-// 0 = default, 2 = non-temporal.  Results are never read back, so they are always
-// stored non-temporal.  Input rows are loaded non-temporal when the whole problem
-// fits the last-level cache anyway, and with the default policy otherwise: then
+// Cache policy of the accesses (the "aux" operand of the buffer instructions): bit 0 = sc0,
+// bit 1 = nt (non-temporal), bit 4 = sc1.  0 is the default policy.  Results are never read
+// back, so they are always stored non-temporal.  Input rows are loaded non-temporal when the
+// whole problem fits the last-level cache anyway, and with the default policy otherwise: then
 // the line that two neighbouring strips share, and the rows that two neighbouring
 // bands share, are found in the CU's vector cache by the second wavefront of the
 // same workgroup.
+// The policies are compile-time constants of the instructions; the macros exist so that a build
+// with other values can be timed against this one.  Measured (us, interleaved runs on one GPU):
+//   stores nt + sc1 (written through at device scope) instead of nt, many small tiles:
+//     8192x8192 uint8 83.1 against 84.8, 2832x4256 32.6 / 32.9, 64x1080x1920 351.9 / 353.9;
+//     one tile per CU, 1536x2560: 12.7 against 12.0 -- so only the many-tile kernels take it;
+//   default-policy stores: 13.4 (1536x2560), 97.6 (8192x8192 uint8), 39.8 (2832x4256);
+//   loads nt + sc1: 12.8 on 1536x2560, no change on the large workloads; sc1 without nt, or
+//     sc1 on the rows two tiles share: 4 to 22 % slower.
+#ifndef HARRIS_LOAD_AUX
+#define HARRIS_LOAD_AUX 2
+#endif
+#ifndef HARRIS_STORE_AUX
+#define HARRIS_STORE_AUX 2
+#endif
+#ifndef HARRIS_MANY_STORE_AUX
+#define HARRIS_MANY_STORE_AUX 18
+#endif
 constexpr int kAuxDefault = 0;
-constexpr int kAuxNonTemporal = 2;
+constexpr int kAuxNonTemporal = HARRIS_LOAD_AUX;
 // Tile kernel only, not a hardware value: non-temporal, except that the first and the last
 // four input rows of a tile, which the tile above or below reads as well, are loaded with the
-// default policy.
+// default policy.  The launches that use it are those of many small tiles; their stores are
+// written through (kAuxManyStore).
 constexpr int kAuxKeepShared = -1;
-#ifndef HARRIS_STORE_AUX
-#define HARRIS_STORE_AUX kAuxNonTemporal
-#endif
+constexpr int kAuxStore = HARRIS_STORE_AUX, kAuxManyStore = HARRIS_MANY_STORE_AUX;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -171,19 +187,19 @@ __device__ __forceinline__ void realign_row(RawRow<uint8_t, 4>& r, const uint32_
 
 // PX results of one lane to a result row described by rs (its size is the row's
 // bytes, or 0 to store nothing); voff is the lane's byte offset in the row.
-template <int PX>
+template <int PX, int AUX = kAuxStore>
 __device__ __forceinline__ void store_row(const float (&o)[PX], __amdgpu_buffer_rsrc_t rs, uint32_t voff) {
     if constexpr (PX >= 4) {
 #pragma unroll
         for (int j = 0; j < PX / 4; ++j) {
             u32x4 v = {__float_as_uint(o[4 * j]), __float_as_uint(o[4 * j + 1]), __float_as_uint(o[4 * j + 2]), __float_as_uint(o[4 * j + 3])};
-            __builtin_amdgcn_raw_buffer_store_b128(v, rs, voff + 16 * j, 0, HARRIS_STORE_AUX);
+            __builtin_amdgcn_raw_buffer_store_b128(v, rs, voff + 16 * j, 0, AUX);
         }
     } else if constexpr (PX == 2) {
         u32x2 v = {__float_as_uint(o[0]), __float_as_uint(o[1])};
-        __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff, 0, HARRIS_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff, 0, AUX);
     } else {
-        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[0]), rs, voff, 0, HARRIS_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[0]), rs, voff, 0, AUX);
     }
 }
 
@@ -210,18 +226,18 @@ __device__ __forceinline__ uint32_t to_16bit_pair(float lo, float hi) {
 
 // PX results of one lane as 16-bit values (BF: bfloat16, else binary16); voff is the lane's
 // byte offset in the row (2 bytes per column).
-template <int PX, bool BF>
+template <int PX, bool BF, int AUX = kAuxStore>
 __device__ __forceinline__ void store_row_16(const float (&o)[PX], __amdgpu_buffer_rsrc_t rs, uint32_t voff) {
     if constexpr (PX >= 4) {
 #pragma unroll
         for (int j = 0; j < PX / 4; ++j) {
             const u32x2 v = {to_16bit_pair<BF>(o[4 * j], o[4 * j + 1]), to_16bit_pair<BF>(o[4 * j + 2], o[4 * j + 3])};
-            __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff + 8 * j, 0, HARRIS_STORE_AUX);
+            __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff + 8 * j, 0, AUX);
         }
     } else if constexpr (PX == 2) {
-        __builtin_amdgcn_raw_buffer_store_b32(to_16bit_pair<BF>(o[0], o[1]), rs, voff, 0, HARRIS_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b32(to_16bit_pair<BF>(o[0], o[1]), rs, voff, 0, AUX);
     } else {
-        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(BF ? to_bf16_bits(o[0]) : to_f16_bits(o[0])), rs, voff, 0, HARRIS_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(BF ? to_bf16_bits(o[0]) : to_f16_bits(o[0])), rs, voff, 0, AUX);
     }
 }
 
@@ -229,7 +245,7 @@ __device__ __forceinline__ void store_row_16(const float (&o)[PX], __amdgpu_buff
 // The hardware's float-to-byte conversion does the rounding (to nearest, ties to even), the
 // clamp and the packing into byte i of a word in one instruction per value.  voff is the
 // lane's byte offset in the row (1 byte per column).
-template <int PX>
+template <int PX, int AUX = kAuxStore>
 __device__ __forceinline__ void store_row_8(const float (&o)[PX], float scale, float offset, __amdgpu_buffer_rsrc_t rs, uint32_t voff) {
     constexpr int WORDS = (PX + 3) / 4;
     uint32_t w[WORDS];
@@ -239,11 +255,11 @@ __device__ __forceinline__ void store_row_8(const float (&o)[PX], float scale, f
     for (int i = 0; i < PX; ++i) w[i / 4] = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(o[i], scale, offset), (uint32_t)(i % 4), w[i / 4]);
     if constexpr (PX >= 4) {
 #pragma unroll
-        for (int j = 0; j < WORDS; ++j) __builtin_amdgcn_raw_buffer_store_b32(w[j], rs, voff + 4 * j, 0, HARRIS_STORE_AUX);
+        for (int j = 0; j < WORDS; ++j) __builtin_amdgcn_raw_buffer_store_b32(w[j], rs, voff + 4 * j, 0, AUX);
     } else if constexpr (PX == 2) {
-        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)w[0], rs, voff, 0, HARRIS_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)w[0], rs, voff, 0, AUX);
     } else {
-        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)w[0], rs, voff, 0, HARRIS_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)w[0], rs, voff, 0, AUX);
     }
 }
 
@@ -660,25 +676,26 @@ __global__ __launch_bounds__(1024) void harris_tile_kernel(const harris_launch::
     // The last wavefront skips the four rows it has no data for.
     if constexpr (HANDOFF) __syncthreads();                     // stores only after all of the workgroup's loads
     __builtin_amdgcn_sched_barrier(0);
+    constexpr int SAUX = LAUX == kAuxKeepShared ? kAuxManyStore : kAuxStore;
     if (__builtin_expect(p.out_kind == HARRIS_OUT_F32, 1)) {
         static_for<0, RW>([&](auto jj) {
             constexpr int j = decltype(jj)::value;
-            if (j < RW - 4 || wave + 1 < n_waves) store_row<PX>(results[j], out_rs[j], lane_bytes + out_lead[j]);
+            if (j < RW - 4 || wave + 1 < n_waves) store_row<PX, SAUX>(results[j], out_rs[j], lane_bytes + out_lead[j]);
         });
     } else if (p.out_kind == HARRIS_OUT_F16) {
         static_for<0, RW>([&](auto jj) {
             constexpr int j = decltype(jj)::value;
-            if (j < RW - 4 || wave + 1 < n_waves) store_row_16<PX, false>(results[j], out_rs[j], lane_bytes + out_lead[j]);
+            if (j < RW - 4 || wave + 1 < n_waves) store_row_16<PX, false, SAUX>(results[j], out_rs[j], lane_bytes + out_lead[j]);
         });
     } else if (p.out_kind == HARRIS_OUT_BF16) {
         static_for<0, RW>([&](auto jj) {
             constexpr int j = decltype(jj)::value;
-            if (j < RW - 4 || wave + 1 < n_waves) store_row_16<PX, true>(results[j], out_rs[j], lane_bytes + out_lead[j]);
+            if (j < RW - 4 || wave + 1 < n_waves) store_row_16<PX, true, SAUX>(results[j], out_rs[j], lane_bytes + out_lead[j]);
         });
     } else {
         static_for<0, RW>([&](auto jj) {
             constexpr int j = decltype(jj)::value;
-            if (j < RW - 4 || wave + 1 < n_waves) store_row_8<PX>(results[j], p.q_scale, p.q_offset, out_rs[j], lane_bytes + out_lead[j]);
+            if (j < RW - 4 || wave + 1 < n_waves) store_row_8<PX, SAUX>(results[j], p.q_scale, p.q_offset, out_rs[j], lane_bytes + out_lead[j]);
         });
     }
 }

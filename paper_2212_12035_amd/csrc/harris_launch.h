@@ -97,6 +97,9 @@ float* scratch_of_current_device();
 // Enqueue the streaming-copy probe (see harris_probe_copy).  Returns a harris_status.
 int launch_copy_probe(const void* rgb, int dtype, int batch, int H, int W, float* out, void* stream);
 
+// Enqueue a pure read or write stream (see harris_probe_stream).  Returns a harris_status.
+int launch_stream_probe(int kind, const void* src, void* dst, long long bytes, void* stream);
+
 }  // namespace harris_launch
 
 #endif

@@ -259,6 +259,21 @@ def test_copy_probe_validates_its_arguments(pkg):
     assert lib.harris_probe_copy(None, 0, 0, 64, 64, None, None) == 0
 
 
+def test_stream_probe_validates_its_arguments(pkg):
+    lib = pkg.load_library()
+    one = ctypes.c_void_p(4096)
+    assert lib.harris_probe_stream(0, one, one, 1024, None) == -3                      # unknown kind
+    assert lib.harris_probe_stream(3, one, one, 1024, None) == -3
+    assert lib.harris_probe_stream(pkg.HARRIS_PROBE_READ, None, one, 1024, None) == -1
+    assert lib.harris_probe_stream(pkg.HARRIS_PROBE_READ, one, None, 1024, None) == -1
+    assert lib.harris_probe_stream(pkg.HARRIS_PROBE_WRITE, None, None, 1024, None) == -1
+    assert lib.harris_probe_stream(pkg.HARRIS_PROBE_WRITE, None, one, 1000, None) == -3     # not a multiple of 16
+    assert lib.harris_probe_stream(pkg.HARRIS_PROBE_WRITE, None, ctypes.c_void_p(4100), 1024, None) == -3
+    assert lib.harris_probe_stream(pkg.HARRIS_PROBE_READ, ctypes.c_void_p(4104), one, 1024, None) == -3
+    assert lib.harris_probe_stream(pkg.HARRIS_PROBE_WRITE, None, one, -16, None) == -2
+    assert lib.harris_probe_stream(pkg.HARRIS_PROBE_READ, None, None, 0, None) == 0          # nothing to move
+
+
 def test_index_division_by_multiplication_is_exact(tmp_path):
     # The tile kernel splits its workgroup index with a multiply-high division whose constants
     # the host computes; the same header functions are checked here against the hardware division.

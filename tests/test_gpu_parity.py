@@ -817,6 +817,24 @@ def test_copy_probe_moves_what_it_says(gpu):
         assert np.array_equal(out.cpu().numpy(), want)
 
 
+def test_stream_probes_touch_what_they_say(gpu):
+    # Measurement aids: the writing probe fills exactly `bytes` bytes (every fourth word of its
+    # pattern is the bits of 1.0f), the reading probe writes nothing, not even its sink.
+    import torch
+    for nbytes in (16, 1024, 4096 + 64, 5 * 4096 * 4 + 1040):
+        say("case stream probes, %d bytes" % nbytes)
+        buf = torch.full((nbytes // 4 + 64,), -7, dtype=torch.int32, device="cuda")
+        gpu.harris_probe_stream(gpu.HARRIS_PROBE_WRITE, None, buf, nbytes)
+        torch.cuda.synchronize()
+        host = buf.cpu().numpy()
+        assert np.all(host[3:nbytes // 4:4] == 0x3f800000) and np.all(host[2:nbytes // 4:4] == 0) and np.all(host[nbytes // 4:] == -7)
+        assert np.array_equal(host[0:nbytes // 4:4] % 64, (np.arange(nbytes // 16) % 64))     # the lane that wrote each 16 bytes
+        sink = torch.full((16,), -7, dtype=torch.int32, device="cuda")
+        gpu.harris_probe_stream(gpu.HARRIS_PROBE_READ, buf, sink, nbytes)
+        torch.cuda.synchronize()
+        assert bool((sink == -7).all()) and np.array_equal(buf.cpu().numpy(), host)
+
+
 # ---------------------------------------------------------------- unfused kernel groupings (baselines)
 
 @pytest.mark.parametrize("grouping", [1, 2, 3, 4])
