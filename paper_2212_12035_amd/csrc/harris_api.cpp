@@ -137,9 +137,14 @@ int plan(int dtype, int out_dtype, int batch, int H, int W, int rgb_align, int o
         static const int kShifted[][2] = {{4, 0}, {8, 0}, {0, 0}};      // the kernels that exist for shifted 8-bit rows
         const int (*list)[2] = in_shifted ? kShifted : need <= 20 ? kShort : need <= 48 ? kMedium : dtype == HARRIS_U8 ? kTall8 : kTall;
         // Tiles of 26 to 32 rows (40 for 8-bit input), and several images with tiles of up to
-        // 48 rows, are faster as many small tiles (960x1280: 6.2 against 6.7 us, 8-bit 5.1 / 5.6;
-        // 1080x1920 8-bit: 5.5 / 5.9, but float32 8.4 / 8.2).
-        const bool small_tiles = (batch > 1 && need <= 48) || (need >= 26 && need <= (dtype == HARRIS_U8 ? 40 : 32));
+        // 48 rows, are faster as many small tiles (960x1280: 6.2 against 6.5 us, 8-bit 5.1 / 5.6;
+        // 1080x1920 8-bit: 5.5 / 5.9, but float32 8.4 / 8.2) -- for float32 input as long as there
+        // are at most two of them per CU: a third one on some CUs costs more than it saves
+        // (900x1600, 525 small tiles: 7.5 us against 6.9 with one tile of 5 x 6 rows per CU;
+        // 1050x1400: 7.7 / 6.9; two images of 720x1280: 7.9 / 7.6).
+        const long long small_count = (long long)batch * n_strips * ((n + 11) / 12);     // tiles of 4 x 4 rows
+        const bool small_tiles = ((batch > 1 && need <= 48) || (need >= 26 && need <= (dtype == HARRIS_U8 ? 40 : 32))) &&
+                                 (dtype == HARRIS_U8 || small_count <= 512);
         long long best = -1;
         for (; (*list)[0] && !small_tiles; ++list) {
             const int rw = (*list)[0];

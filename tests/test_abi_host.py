@@ -120,6 +120,12 @@ def test_plan_defaults_follow_the_problem_size(pkg):
     # tiles of 26 to 32 rows (40 for 8-bit input) give way to many small tiles
     assert pkg.harris_plan(pkg.HARRIS_F32, 1, 960, 1280)[1] == 6 * 80 and pkg.harris_plan(pkg.HARRIS_F32, 1, 1080, 1920)[1] <= 256
     assert pkg.harris_plan(pkg.HARRIS_U8, 1, 1080, 1920)[1] == 8 * 90
+    # ... for float32 input only while at most two small tiles come to lie on a CU (512 in all): 900x1600 would be 525
+    mid, blocks = pkg.harris_plan(pkg.HARRIS_F32, 1, 900, 1600)
+    assert (mid["rows"], mid["waves_per_block"]) == (6, 5) and blocks == 7 * 35 and mid["flags"] & pkg.HARRIS_TUNE_FLAG_HANDOFF
+    assert pkg.harris_plan(pkg.HARRIS_F32, 1, 1024, 1280)[1] == 6 * 85
+    two, blocks = pkg.harris_plan(pkg.HARRIS_F32, 2, 720, 1280)
+    assert (two["rows"], two["waves_per_block"]) == (5, 8) and blocks == 2 * 6 * 20
     several, blocks = pkg.harris_plan(pkg.HARRIS_F32, 4, 480, 640)
     assert (several["rows"], several["waves_per_block"]) == (4, 4) and blocks == 4 * 3 * 40
     # beyond one tile per CU: many tiles, non-temporal loads except the rows two tiles share, which stay in L2,
