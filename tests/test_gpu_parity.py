@@ -50,7 +50,7 @@ ROUNDING_LIMIT = 64.0       # in units of float32 eps * max trace^2; a correct k
 def rounding_distance(oracle, got, rgb, k=K, scale=1.0, window=0, nthreads=4):
     """max|gpu - float64 referee| in units of float32 eps times the largest trace^2.
 
-    The bar of the task is far above float32 rounding (observed errors are a few thousandths of
+    The parity bar is far above float32 rounding (observed errors are a few thousandths of
     it), so a wrong rounding path or a small lost term could hide below it.  Every term of the
     coarsity is bounded by trace^2: a correct float32 evaluation, in any order and with or
     without fused multiply-adds, stays within a few eps * trace^2 of the exact result."""
