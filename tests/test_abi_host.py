@@ -394,6 +394,29 @@ def test_binding_refuses_host_tensors(pkg):
         pkg.harris_coarsity(torch.zeros(1, 3, 8, 8))
 
 
+def test_sweep_candidates_are_launch_shapes_the_library_knows(pkg):
+    # The launch-shape sweep times the planner's choice against candidates; every candidate must be a
+    # shape harris_plan accepts or cleanly refuses (never one that would only fail at launch), the
+    # default must come first, and for a one-tile-per-CU size the planner's own choice must be among them.
+    from paper_2212_12035_amd import sweep
+    for dtype in (pkg.HARRIS_F32, pkg.HARRIS_U8):
+        for B, H, W in ((1, 1536, 2560), (1, 900, 1600), (4, 480, 640), (64, 1080, 1920), (1, 8192, 8192)):
+            cands = sweep.candidates(pkg, dtype, B, H, W)
+            assert cands[0][0] == "default" and len({name for name, _ in cands}) == len(cands)
+            accepted = []
+            for name, t in cands:
+                try:
+                    shape, blocks = pkg.harris_plan(dtype, B, H, W, tuning=t)
+                    assert blocks > 0 and shape["schedule"] == pkg.HARRIS_SCHEDULE_TILES and shape["px"] == 4
+                    accepted.append((shape["rows"], shape["waves_per_block"]))
+                except pkg.HarrisError as e:
+                    assert e.status == -3, name
+            assert len(accepted) >= 8
+    chosen = pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560)[0]
+    shapes = [pkg.harris_plan(pkg.HARRIS_F32, 1, 1536, 2560, tuning=t)[0] for _, t in sweep.candidates(pkg, pkg.HARRIS_F32, 1, 1536, 2560)[1:]]
+    assert any((s["rows"], s["waves_per_block"], s["flags"] & pkg.HARRIS_TUNE_FLAG_HANDOFF) == (chosen["rows"], chosen["waves_per_block"], chosen["flags"] & pkg.HARRIS_TUNE_FLAG_HANDOFF) for s in shapes)
+
+
 def test_benchmark_refuses_more_than_one_gpu():
     # The benchmark measures one GPU; asked for more it says so and exits before touching a device.
     import subprocess
