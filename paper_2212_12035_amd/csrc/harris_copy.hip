@@ -18,13 +18,12 @@
 
 namespace {
 
-#ifndef HARRIS_PROBE_LOAD_AUX
-#define HARRIS_PROBE_LOAD_AUX 2
-#endif
-#ifndef HARRIS_PROBE_STORE_AUX
-#define HARRIS_PROBE_STORE_AUX 2
-#endif
-constexpr int kNonTemporal = HARRIS_PROBE_LOAD_AUX, kStoreNonTemporal = HARRIS_PROBE_STORE_AUX;
+// Cache policies (the "aux" operand): 0 default, 2 non-temporal, 18 non-temporal and written through
+// at device scope.  Loads are always non-temporal.  The copy probe's stores take the policy that is
+// fastest for the size at hand, so that the probe stays the best plain copy known (measured, us:
+// 63 MB 11.2 default / 11.4 nt / 11.6 nt+sc1; 193 MB 32.9 / 31.0 / 31.9; 2.1 GB 350 / 330 / 318;
+// 469 MB of uint8 input 78.7 / 74.7 / 71.9).
+constexpr int kNonTemporal = 2, kStoreNonTemporal = 2, kStoreDefault = 0, kStoreWriteThrough = 18;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, uint32_t bytes) {
@@ -32,7 +31,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* p, uint32_t b
 }
 
 // float32: a chunk is 256 elements, 4 per lane.
-template <int kRun>
+template <int kRun, int kStoreAux>
 __global__ __launch_bounds__(256) void copy_probe_f32(const float* rgb, float* out, unsigned long long count, unsigned long long plane,
                                                       unsigned long long chunks_per_image) {
     const unsigned lane = threadIdx.x % 64;
@@ -60,7 +59,7 @@ __global__ __launch_bounds__(256) void copy_probe_f32(const float* rgb, float* o
         w.y = __float_as_uint(__uint_as_float(v[r][0].y) + __uint_as_float(v[r][1].y) + __uint_as_float(v[r][2].y));
         w.z = __float_as_uint(__uint_as_float(v[r][0].z) + __uint_as_float(v[r][1].z) + __uint_as_float(v[r][2].z));
         w.w = __float_as_uint(__uint_as_float(v[r][0].w) + __uint_as_float(v[r][1].w) + __uint_as_float(v[r][2].w));
-        __builtin_amdgcn_raw_buffer_store_b128(w, rsrc(dst + chunk[r] * 256, live[r] * 4u), lane * 16u, 0, kStoreNonTemporal);
+        __builtin_amdgcn_raw_buffer_store_b128(w, rsrc(dst + chunk[r] * 256, live[r] * 4u), lane * 16u, 0, kStoreAux);
     }
 }
 
@@ -68,6 +67,7 @@ __global__ __launch_bounds__(256) void copy_probe_f32(const float* rgb, float* o
 // wavefront then turns its 3 x 1 KB around in a private piece of LDS so that lane l holds elements
 // 256 q + 4 l .. + 3 for q = 0..3, and each of its four 128-bit stores writes one contiguous kilobyte
 // (stores of 16 bytes per lane at a stride of 64 bytes were measured 4 times slower).
+template <int kStoreAux>
 __global__ __launch_bounds__(256) void copy_probe_u8(const uint8_t* rgb, float* out, unsigned long long count, unsigned long long plane,
                                                      unsigned long long chunks_per_image) {
     __shared__ uint32_t turn[4][3][256];                       // [wavefront][plane][dword of the chunk]
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void copy_probe_u8(const uint8_t* rgb, float* 
         w.y = __float_as_uint((float)(((a >> 8) & 0xffu) + ((b >> 8) & 0xffu) + ((c >> 8) & 0xffu)));
         w.z = __float_as_uint((float)(((a >> 16) & 0xffu) + ((b >> 16) & 0xffu) + ((c >> 16) & 0xffu)));
         w.w = __float_as_uint((float)((a >> 24) + (b >> 24) + (c >> 24)));
-        __builtin_amdgcn_raw_buffer_store_b128(w, drs, 1024u * q + lane * 16u, 0, kStoreNonTemporal);
+        __builtin_amdgcn_raw_buffer_store_b128(w, drs, 1024u * q + lane * 16u, 0, kStoreAux);
     }
 }
 
@@ -173,8 +173,17 @@ int launch_copy_probe(const void* rgb, int dtype, int batch, int H, int W, float
     // that the probe stays the best plain copy known here.
     const unsigned long long bytes = (unsigned long long)batch * count * (dtype == HARRIS_U8 ? 7 : 16);
     const unsigned reserve = dtype == HARRIS_U8 ? 16u << 10 : bytes > (1ULL << 30) ? 64u << 10 : bytes > (400ULL << 20) ? 52u << 10 : bytes > (128ULL << 20) ? 36u << 10 : 0u;
-    if (dtype == HARRIS_U8) hipLaunchKernelGGL(copy_probe_u8, grid, block, reserve, s, static_cast<const uint8_t*>(rgb), out, count, plane, chunks);
-    else hipLaunchKernelGGL((copy_probe_f32<2>), grid, block, reserve, s, static_cast<const float*>(rgb), out, count, plane, chunks);
+    const bool large = bytes > (400ULL << 20);
+    if (dtype == HARRIS_U8) {
+        const uint8_t* src = static_cast<const uint8_t*>(rgb);
+        if (large) hipLaunchKernelGGL((copy_probe_u8<kStoreWriteThrough>), grid, block, reserve, s, src, out, count, plane, chunks);
+        else hipLaunchKernelGGL((copy_probe_u8<kStoreNonTemporal>), grid, block, reserve, s, src, out, count, plane, chunks);
+    } else {
+        const float* src = static_cast<const float*>(rgb);
+        if (large) hipLaunchKernelGGL((copy_probe_f32<2, kStoreWriteThrough>), grid, block, reserve, s, src, out, count, plane, chunks);
+        else if (bytes > (128ULL << 20)) hipLaunchKernelGGL((copy_probe_f32<2, kStoreNonTemporal>), grid, block, reserve, s, src, out, count, plane, chunks);
+        else hipLaunchKernelGGL((copy_probe_f32<2, kStoreDefault>), grid, block, reserve, s, src, out, count, plane, chunks);
+    }
     return hipGetLastError() == hipSuccess ? HARRIS_OK : HARRIS_ERR_LAUNCH;
 }
 

@@ -817,6 +817,25 @@ def test_copy_probe_moves_what_it_says(gpu):
         assert np.array_equal(out.cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("B,H,W,u8", [(8, 1080, 1920, False), (16, 1080, 1920, False), (1, 8192, 4096, True), (1, 8192, 8192, True)])
+def test_copy_probe_at_the_sizes_where_its_store_policy_changes(gpu, B, H, W, u8):
+    # Above 128 MB and above 400 MB the probe stores with other cache policies (kernels of their own).
+    import torch
+    say("case copy probe %s %dx3x%dx%d" % ("u8" if u8 else "f32", B, H, W))
+    gen = torch.Generator(device="cuda").manual_seed(H + W + B)
+    if u8:
+        rgb = torch.randint(0, 256, (B, 3, H, W), dtype=torch.uint8, device="cuda", generator=gen)
+    else:
+        rgb = torch.randint(0, 1024, (B, 3, H, W), device="cuda", generator=gen).float() / 1024.0
+    n = (H - 4) * (W - 4)
+    flat = rgb.reshape(B, 3, H * W)[:, :, :n].float()
+    want = (flat[:, 0] + flat[:, 1] + flat[:, 2]).reshape(B, H - 4, W - 4)       # exact in float32 for these values
+    out = torch.full((B, H - 4, W - 4), float("nan"), device="cuda")
+    gpu.harris_probe_copy(rgb, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, want)
+
+
 def test_stream_probes_touch_what_they_say(gpu):
     # Measurement aids: the writing probe fills exactly `bytes` bytes (every fourth word of its
     # pattern is the bits of 1.0f), the reading probe writes nothing, not even its sink.
