@@ -35,9 +35,9 @@ SETTLE_MS = 20.0               # untimed launches before the timed region, in GP
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files without comments, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "0e2088437eaf2e6e0757a73c7206147fc2cbe4d674ed6928a0a3853e14217d61"
-TRAFFIC_BYTES = {"noise_f32_1536x2560": 65087014, "rects_f32_64x1080x1920": 2138785014,
-                 "blobs_f32_2832x4256": 196596180, "noise_u8_8192x8192": 474916242}
+TRAFFIC_SOURCES_SHA256 = "ad4e8e2f54c045f56e5cca82adfb8dcca98a79e05008b379472c6eae4928f06a"
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 65088947, "rects_f32_64x1080x1920": 2138713412,
+                 "blobs_f32_2832x4256": 196612675, "noise_u8_8192x8192": 474946240}
 
 
 def kernel_sources_sha256():
