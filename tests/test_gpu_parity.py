@@ -926,6 +926,43 @@ def test_runs_on_a_side_stream(gpu, oracle):
     check(out.cpu().numpy(), oracle.harris(rgb, K))
 
 
+def test_concurrent_calls_from_host_threads_on_their_own_streams(gpu, oracle):
+    # The library keeps no state between calls: four host threads, each with a stream, inputs and
+    # results of its own (default stream priority), launch different problems at the same time,
+    # so that kernels of several calls share the GPU; every result is checked against the oracle.
+    import threading
+    import torch
+    jobs = [(hi.white_noise_f32(500, 2, 300, 1000), None),
+            (hi.white_noise_u8(501, 1, 400, 1203), None),
+            (hi.rectangles_f32(502, 1, 700, 1500, n_rect=20), dict(schedule=2, px=4, rows=8, waves_per_block=9, flags=gpu.HARRIS_TUNE_FLAG_HANDOFF)),
+            (hi.white_noise_f32(503, 3, 90, 517), dict(schedule=1, rows=16, prefetch=3, waves_per_block=2))]
+    srcs = [torch.from_numpy(rgb).cuda() for rgb, _ in jobs]
+    outs = [torch.empty((rgb.shape[0], rgb.shape[2] - 4, rgb.shape[3] - 4), device="cuda") for rgb, _ in jobs]
+    streams = [torch.cuda.Stream() for _ in jobs]
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(i):
+        try:
+            with torch.cuda.stream(streams[i]):
+                for _ in range(40):
+                    gpu.harris_coarsity_ex(srcs[i], K, tuning=jobs[i][1], out=outs[i])
+            streams[i].synchronize()
+        except Exception as e:                                   # reported by the main thread
+            errors.append((i, e))
+
+    say("case four host threads, four streams, 40 launches each")
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(len(jobs))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for (rgb, _), out in zip(jobs, outs):
+        check(out.cpu().numpy(), oracle.harris(rgb, K))
+
+
 def test_captured_in_a_graph_and_replayed(gpu, oracle):
     # The library allocates nothing and never synchronises, so its launches can be captured.
     # A graph of three launches (barrier hand-over, ready flags with 64 KB of LDS reserved, 8-bit
