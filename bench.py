@@ -281,6 +281,31 @@ def main():
             streams[name + "_us"] = round(us, 3)
             streams[name + "_GB/s"] = round(sbytes / (us * 1e-6) / 1e9, 1)
         del bufs
+        # What a kernel launch costs the GPU by itself: launches that touch no memory, replayed from
+        # a captured graph so that the host's launch rate does not bound their period.
+        def idle():
+            rc = lib.harris_probe_stream(pkg.HARRIS_PROBE_NONE, None, None, 0, ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream))
+            if rc != 0:
+                raise RuntimeError(pkg.harris_strerror(rc))
+        side = torch.cuda.Stream(dev)
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            idle()                                # the kernel is loaded before the capture
+        side.synchronize()
+        graph, nodes, replays = torch.cuda.CUDAGraph(), 500, 8
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(nodes):
+                idle()
+        graph.replay()
+        torch.cuda.synchronize(dev)
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record(stream)
+        for _ in range(replays):
+            graph.replay()
+        g1.record(stream)
+        torch.cuda.synchronize(dev)
+        streams["idle_launch_us"] = round(g0.elapsed_time(g1) * 1e3 / (nodes * replays), 3)
+        streams["idle_launch_what"] = "harris_probe_stream(HARRIS_PROBE_NONE): a launch that touches no memory, %d of them in a graph, %d replays" % (nodes, replays)
 
     # Correctness of what was timed: pair 0 against the oracle (also the CPU baseline).
     got = outs[0].float().cpu().numpy()

@@ -119,11 +119,16 @@ int harris_probe_copy(const void* rgb, int dtype, int batch, int H, int W, float
  *                            writable bytes (a sink that keeps the loads alive and stays untouched).
  *   kind HARRIS_PROBE_WRITE  every byte of dst[0 .. bytes) is written once with a pattern of no
  *                            meaning; src is ignored.
+ *   kind HARRIS_PROBE_NONE   a launch of 256 workgroups of 256 threads that touch no memory: what
+ *                            the GPU needs for a kernel launch by itself (many of them in a
+ *                            captured graph give the period that the host's launch rate does not
+ *                            bound).  src, dst and bytes (>= 0) are ignored and may be NULL and 0.
  * src and dst are device pointers, 16-byte aligned, bytes a multiple of 16 (else HARRIS_ERR_ARG);
- * bytes == 0 succeeds without work.
+ * bytes == 0 succeeds without work (kinds READ and WRITE).
  */
 #define HARRIS_PROBE_READ 1
 #define HARRIS_PROBE_WRITE 2
+#define HARRIS_PROBE_NONE 3
 int harris_probe_stream(int kind, const void* src, void* dst, long long bytes, void* stream);
 
 #ifdef __cplusplus

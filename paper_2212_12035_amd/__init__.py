@@ -13,5 +13,5 @@ from .binding import (  # noqa: F401
     HarrisError, HarrisTuning, HarrisLayout, library_path, load_library, harris_coarsity_pitched,
     harris_coarsity, harris_coarsity_u8, harris_coarsity_ex, harris_plan, harris_strerror, harris_version,
     harris_coarsity_grouped, harris_grouped_workspace_bytes, harris_probe_copy,
-    harris_coarsity_grouped_static, HARRIS_GROUPED_SCRATCH_BYTES, harris_probe_stream, HARRIS_PROBE_READ, HARRIS_PROBE_WRITE,
+    harris_coarsity_grouped_static, HARRIS_GROUPED_SCRATCH_BYTES, harris_probe_stream, HARRIS_PROBE_READ, HARRIS_PROBE_WRITE, HARRIS_PROBE_NONE,
 )

@@ -251,15 +251,17 @@ def harris_probe_copy(rgb, out=None, stream=None):
     return out
 
 
-HARRIS_PROBE_READ, HARRIS_PROBE_WRITE = 1, 2
+HARRIS_PROBE_READ, HARRIS_PROBE_WRITE, HARRIS_PROBE_NONE = 1, 2, 3
 
 
 def harris_probe_stream(kind: int, src, dst, nbytes: int, stream=None):
-    """A pure read (kind 1: src -> nowhere) or write (kind 2: pattern -> dst) stream of nbytes bytes."""
+    """A pure read (kind 1: src -> nowhere) or write (kind 2: pattern -> dst) stream of nbytes bytes, or a launch that
+    moves nothing (kind 3: src, dst may be None)."""
     import torch
-    with torch.cuda.device(dst.device):
-        _check(load_library().harris_probe_stream(kind, src.data_ptr() if src is not None else None, dst.data_ptr(), nbytes,
-                                                  _stream_ptr(stream, dst.device)))
+    device = dst.device if dst is not None else torch.device("cuda", torch.cuda.current_device())
+    with torch.cuda.device(device):
+        _check(load_library().harris_probe_stream(kind, src.data_ptr() if src is not None else None,
+                                                  dst.data_ptr() if dst is not None else None, nbytes, _stream_ptr(stream, device)))
 
 
 def harris_grouped_workspace_bytes(grouping: int, batch: int, H: int, W: int) -> int:

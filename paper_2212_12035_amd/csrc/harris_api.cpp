@@ -461,8 +461,9 @@ int harris_probe_copy(const void* rgb, int dtype, int batch, int H, int W, float
 }
 
 int harris_probe_stream(int kind, const void* src, void* dst, long long bytes, void* stream) {
-    if (kind != HARRIS_PROBE_READ && kind != HARRIS_PROBE_WRITE) return HARRIS_ERR_ARG;
+    if (kind != HARRIS_PROBE_READ && kind != HARRIS_PROBE_WRITE && kind != HARRIS_PROBE_NONE) return HARRIS_ERR_ARG;
     if (bytes < 0) return HARRIS_ERR_SHAPE;
+    if (kind == HARRIS_PROBE_NONE) return harris_launch::launch_stream_probe(kind, nullptr, nullptr, 0, stream);
     if (bytes == 0) return HARRIS_OK;
     if (dst == nullptr || (kind == HARRIS_PROBE_READ && src == nullptr)) return HARRIS_ERR_NULL;
     if (bytes % 16 != 0 || pointer_alignment(dst) < 16 || (kind == HARRIS_PROBE_READ && pointer_alignment(src) < 16)) return HARRIS_ERR_ARG;

@@ -143,6 +143,11 @@ __global__ __launch_bounds__(256) void write_probe(uint32_t* dst, unsigned long 
     }
 }
 
+// A launch that moves nothing: `armed` is always 0, so no thread touches memory.
+__global__ __launch_bounds__(256) void idle_probe(uint32_t* sink, uint32_t armed) {
+    if (armed != 0u && threadIdx.x == 0) sink[0] = armed;
+}
+
 }  // namespace
 
 namespace harris_launch {
@@ -152,6 +157,10 @@ int launch_stream_probe(int kind, const void* src, void* dst, long long bytes, v
     const unsigned long long chunks = ((unsigned long long)bytes + 1023) / 1024, waves = (chunks + kRun - 1) / kRun, blocks = (waves + 3) / 4;
     if (blocks > 0x7fffffffULL) return HARRIS_ERR_SHAPE;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (kind == HARRIS_PROBE_NONE) {
+        hipLaunchKernelGGL(idle_probe, dim3(256), dim3(256), 0, s, static_cast<uint32_t*>(nullptr), 0u);
+        return hipGetLastError() == hipSuccess ? HARRIS_OK : HARRIS_ERR_LAUNCH;
+    }
     if (kind == HARRIS_PROBE_READ)
         hipLaunchKernelGGL((read_probe<kRun>), dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const uint32_t*>(src), static_cast<uint32_t*>(dst), chunks, (unsigned long long)bytes, 0x9e3779b9u);
     else

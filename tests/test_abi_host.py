@@ -269,7 +269,8 @@ def test_stream_probe_validates_its_arguments(pkg):
     lib = pkg.load_library()
     one = ctypes.c_void_p(4096)
     assert lib.harris_probe_stream(0, one, one, 1024, None) == -3                      # unknown kind
-    assert lib.harris_probe_stream(3, one, one, 1024, None) == -3
+    assert lib.harris_probe_stream(4, one, one, 1024, None) == -3
+    assert lib.harris_probe_stream(pkg.HARRIS_PROBE_NONE, None, None, -1, None) == -2     # the idle launch ignores all but the sign
     assert lib.harris_probe_stream(pkg.HARRIS_PROBE_READ, None, one, 1024, None) == -1
     assert lib.harris_probe_stream(pkg.HARRIS_PROBE_READ, one, None, 1024, None) == -1
     assert lib.harris_probe_stream(pkg.HARRIS_PROBE_WRITE, None, None, 1024, None) == -1

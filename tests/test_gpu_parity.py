@@ -852,6 +852,21 @@ def test_stream_probes_touch_what_they_say(gpu):
         gpu.harris_probe_stream(gpu.HARRIS_PROBE_READ, buf, sink, nbytes)
         torch.cuda.synchronize()
         assert bool((sink == -7).all()) and np.array_equal(buf.cpu().numpy(), host)
+    say("case idle launch, eager and in a graph")
+    guard = torch.full((1024,), -7, dtype=torch.int32, device="cuda")
+    gpu.harris_probe_stream(gpu.HARRIS_PROBE_NONE, None, None, 0)          # no pointers: it touches no memory
+    gpu.harris_probe_stream(gpu.HARRIS_PROBE_NONE, guard, guard, 4096)      # and ignores those it gets
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(50):
+            gpu.harris_probe_stream(gpu.HARRIS_PROBE_NONE, None, None, 0)
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    assert bool((guard == -7).all())
 
 
 # ---------------------------------------------------------------- unfused kernel groupings (baselines)
