@@ -35,9 +35,9 @@ SETTLE_MS = 20.0               # untimed launches before the timed region, in GP
 
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (summaries under profiles/), valid only
 # for the kernel sources they were taken with: (sha256 of the csrc files without comments, {workload: bytes}).
-TRAFFIC_SOURCES_SHA256 = "ad4e8e2f54c045f56e5cca82adfb8dcca98a79e05008b379472c6eae4928f06a"
-TRAFFIC_BYTES = {"noise_f32_1536x2560": 65088947, "rects_f32_64x1080x1920": 2138713412,
-                 "blobs_f32_2832x4256": 196612675, "noise_u8_8192x8192": 474946240}
+TRAFFIC_SOURCES_SHA256 = "afb62ddae48fa5f0140fe70a49733a13eb522ec8c8da10fe2dfd692c10a8c2e7"
+TRAFFIC_BYTES = {"noise_f32_1536x2560": 65109553, "rects_f32_64x1080x1920": 2138767251,
+                 "blobs_f32_2832x4256": 196600535, "noise_u8_8192x8192": 474898329}
 
 
 def kernel_sources_sha256():
