@@ -794,6 +794,64 @@ def test_random_shapes_layouts_and_launch_shapes(gpu, oracle):
         assert bool(torch.isnan(rest).all())
 
 
+def test_random_tile_shapes_policies_and_reservations(gpu, oracle):
+    # 80 seeded cases on larger images (several tiles down and across, ragged last ones) with a
+    # tile shape drawn from everything the library has kernels for: 4 to 10 rows per wavefront, 2 to
+    # 16 wavefronts, each load policy, the barrier or the ready flags, any LDS reservation; shapes
+    # the library rejects fall back to its own plan.  Float32 and 8-bit input, float32 and 16-bit
+    # results, padded rows and offset bases; guard bands and padding must stay untouched.
+    import torch
+    rng = np.random.default_rng(20221213)
+    for case in range(80):
+        B = int(rng.integers(1, 4)); H = int(rng.choice([rng.integers(30, 200), rng.integers(200, 500)]))
+        W = int(rng.choice([rng.integers(40, 300), rng.integers(300, 1300)]))
+        if rng.random() < 0.5:
+            W = max(8, W // 4 * 4)
+        u8 = bool(rng.random() < 0.4)
+        fmt = str(rng.choice(["f32", "f32", "f16", "bf16"]))
+        scale = float(rng.choice([1.0, S12])); window = int(rng.integers(0, 2)); k = float(rng.choice([0.04, 0.06]))
+        n, m = H - 4, W - 4
+        in_pitch = W + int(rng.choice([0, 0, 4, 7, 1, 33])); in_off = int(rng.choice([0, 0, 4, 1, 3]))
+        out_pitch = m + int(rng.choice([0, 0, 4, 5, 1, 3])); out_off = int(rng.choice([0, 0, 4, 2, 1, 3]))
+        rgb = hi.white_noise_u8(3000 + case, B, H, W) if u8 else hi.rectangles_f32(3000 + case, B, H, W, n_rect=12)
+        store = torch.zeros(B * 3 * H * in_pitch + 64, dtype=torch.uint8 if u8 else torch.float32, device="cuda")
+        src = store[in_off:in_off + B * 3 * H * in_pitch].view(B, 3, H, in_pitch)[:, :, :, :W]
+        src.copy_(torch.from_numpy(rgb).cuda())
+        tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[fmt]
+        flat = torch.full((B * n * out_pitch + 64,), float("nan"), dtype=tdt, device="cuda")
+        view = flat[out_off:out_off + B * n * out_pitch].view(B, n, out_pitch)[:, :, :m]
+        flags = 0
+        if rng.random() < 0.5:
+            flags |= gpu.HARRIS_TUNE_STREAM_LOADS
+        if rng.random() < 0.3:
+            flags |= gpu.HARRIS_TUNE_STREAM_LOADS | gpu.HARRIS_TUNE_KEEP_SHARED_ROWS
+        if rng.random() < 0.3 and not u8:
+            flags |= gpu.HARRIS_TUNE_FLAG_HANDOFF
+        tune = dict(schedule=2, rows=int(rng.choice([4, 5, 6, 8, 9, 10])), waves_per_block=int(rng.integers(2, 17)), flags=flags,
+                    lds_kb=int(rng.choice([0, 0, 28, 36, 48, 64])))
+        say("case random tiles %d: %s %dx3x%dx%d -> %s scale=%g window=%d k=%g pitches %d/%d offsets %d/%d tuning %s"
+            % (case, "u8" if u8 else "f32", B, H, W, fmt, scale, window, k, in_pitch, out_pitch, in_off, out_off, tune))
+        try:
+            gpu.harris_coarsity_typed(src, view, k, scale, window, tuning=tune)
+        except gpu.HarrisError as e:
+            assert e.status == -3
+            say("   (no kernel for this shape and layout: the library's own plan instead)")
+            gpu.harris_coarsity_typed(src, view, k, scale, window)
+        torch.cuda.synchronize()
+        want = oracle.harris(rgb, k, scale, window)
+        got = view.float().cpu().numpy()
+        bound = 1e-4 * float(np.abs(want).max()) + 1e-6
+        if fmt == "f32":
+            check(got, want)
+        else:
+            want16 = _as_f32(oracle.round_to_16bit(want, fmt), fmt)
+            with np.errstate(invalid="ignore"):                      # a value beyond binary16's range is infinite on both sides
+                assert np.all((np.abs(got.astype(np.float64) - want16) <= bound + _ulp16(want, fmt)) | (np.isinf(want16) & (got == want16)))
+        rest = flat.clone()
+        rest[out_off:out_off + B * n * out_pitch].view(B, n, out_pitch)[:, :, :m] = float("nan")
+        assert bool(torch.isnan(rest).all())
+
+
 # ---------------------------------------------------------------- the streaming-copy probe (measurement aid)
 
 def test_copy_probe_moves_what_it_says(gpu):
